@@ -1,0 +1,206 @@
+/*
+ * oscar.h -- C ABI of the MI355X (gfx950) OScaR KV-cache library.
+ *
+ * OScaR ("Omni-Scaled Canalized Rotation") compresses the key/value cache of a
+ * decoder-only transformer to 2 or 4 bits:
+ *   keys  : Hadamard rotation on the head dimension (Canalized Rotation), then
+ *           division by the per-token L2 norm (Omni-Token Scaling, the norm is
+ *           kept as metadata), then block-wise per-channel asymmetric uniform
+ *           quantization over groups of G_k tokens;
+ *   values: per-token asymmetric uniform quantization over groups of G_v
+ *           channels (no run-time rotation or scaling);
+ *   new tokens wait in a 16-bit residual window of R tokens and are quantized
+ *   block-wise once R of them have accumulated;
+ *   decode attention rotates the query the same way, dequantizes on the fly,
+ *   multiplies the key logits by the stored token norms and runs
+ *   softmax(q K^T) V over packed + residual tokens.
+ * (Paper: Sec. "Block-Wise Per-Channel Quantization" Eq. 3-4; Sec. "The OScaR
+ * Framework"; Sec. "Efficient System Design and CUDA Implementations";
+ * App. "Implementation Details of OScaR's CUDA Kernels"; Algorithm
+ * "The OScaR algorithm".)
+ *
+ * Conventions
+ *  - Every pointer named "device" is GPU memory owned by the caller; the library
+ *    never allocates, frees or retains device memory and keeps no global state.
+ *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
+ *    the default stream). They do not synchronize and never read device memory
+ *    on the host (oscar_debug_dump excepted), which is why upper bounds on
+ *    sequence lengths are passed as hints.
+ *  - Return value: OSCAR_OK (0) or a negative OSCAR_ERR_* code. When an argument
+ *    check fails nothing is enqueued. No C++ exception crosses this boundary.
+ *  - Calls that touch the same cache on different streams race; order them.
+ */
+#ifndef OSCAR_H_
+#define OSCAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OSCAR_VERSION 100 /* 0.1.0 */
+
+/* element types */
+enum { OSCAR_F32 = 0, OSCAR_BF16 = 1, OSCAR_F16 = 2 };
+/* zero-point form: integer z = round(-min/Delta) (Eq. 3-4) or float zero = min */
+enum { OSCAR_ZP_INT = 0, OSCAR_ZP_MIN = 1 };
+/* scope of the token norm: one norm per (token, kv head), or one per token over all kv heads */
+enum { OSCAR_NORM_PER_HEAD = 0, OSCAR_NORM_ALL_KV_HEADS = 1 };
+/* status codes */
+enum {
+  OSCAR_OK = 0,
+  OSCAR_ERR_INVALID_ARG = -1, /* null pointer, negative size, inconsistent fields */
+  OSCAR_ERR_UNSUPPORTED = -2, /* valid in the paper's terms but not built (see oscar_config) */
+  OSCAR_ERR_CAPACITY = -3,    /* the hint shows a sequence would outgrow its block table */
+  OSCAR_ERR_WORKSPACE = -4,   /* workspace missing or too small */
+  OSCAR_ERR_HIP = -5          /* a HIP runtime call or kernel launch failed */
+};
+/* flags of oscar_quantize_append */
+enum {
+  OSCAR_APPEND_EAGER = 1u /* prefill rule: quantize every completed block at once */
+};
+
+/* Parameters of the method (Algorithm "The OScaR algorithm": G, R, d_h; Eq. 3-4: b).
+ * Checked on every call. Built: head_dim 128; bits 2|4; k_group 32|64|128;
+ * v_group 32|64|128; page_size 128; io_dtype any; meta_dtype F16|F32;
+ * zp_mode OSCAR_ZP_INT; norm_scope OSCAR_NORM_PER_HEAD; n_q_heads/n_kv_heads <= 8.
+ * Anything else returns OSCAR_ERR_UNSUPPORTED. */
+typedef struct oscar_config {
+  int32_t head_dim;    /* d_h */
+  int32_t n_q_heads;   /* query heads; multiple of n_kv_heads; q head h reads kv head h / g */
+  int32_t n_kv_heads;
+  int32_t bits;        /* b */
+  int32_t k_group;     /* G for keys: tokens per per-channel group; divides page_size */
+  int32_t v_group;     /* G for values: channels per per-token group; divides head_dim */
+  int32_t page_size;   /* R: residual length = flush block = tokens per page */
+  int32_t io_dtype;    /* element type of k, v, q and of the value residual */
+  int32_t meta_dtype;  /* storage type of Delta, zero-point and token norm */
+  int32_t zp_mode;
+  int32_t norm_scope;
+} oscar_config;
+
+/* The paged cache. Plain data; every pointer is DEVICE memory the caller
+ * allocated with the sizes oscar_cache_sizes reports (256-byte aligned).
+ *
+ * Packed part: logical page p of sequence b is physical page block_table[b][p];
+ * a physical page holds R tokens of ALL kv heads; pools are indexed
+ * [physical page][kv head][bytes]:
+ *   k_codes : R rows (tokens) of head_dim*bits/8 bytes, channel j at bit j*bits (little endian)
+ *   k_meta  : Delta[R/k_group][head_dim] then zero[R/k_group][head_dim]      (meta_dtype)
+ *   k_norms : n[R]                                                           (meta_dtype)
+ *   v_codes : head_dim rows (channels) of R*bits/8 bytes, token t at bit t*bits
+ *   v_meta  : Delta[head_dim/v_group][R] then zero[head_dim/v_group][R]      (meta_dtype)
+ * Residual part, indexed [sequence][kv head]:
+ *   res_k   : [R][head_dim] fp16, rotated and normalized keys K_u
+ *   res_v   : [R][head_dim] io_dtype
+ *   res_norm: [R] meta_dtype
+ * State: seq_lens[b] = tokens held for sequence b; res_lens[b] of them (0..R,
+ * the most recent ones) are in the residual, the rest fill
+ * (seq_lens[b]-res_lens[b])/R whole pages. A fresh cache has both arrays zeroed.
+ * dev_status (may be NULL): a device int32 the kernels set to OSCAR_ERR_CAPACITY
+ * when a sequence would need more than max_pages_per_seq pages; that append is
+ * dropped for that sequence. */
+typedef struct oscar_cache {
+  oscar_config cfg;
+  int32_t batch;
+  int32_t max_pages_per_seq;
+  int32_t num_pages;
+  int32_t reserved_;
+  void *k_codes, *k_meta, *k_norms, *v_codes, *v_meta;
+  void *res_k, *res_v, *res_norm;
+  int32_t *block_table; /* [batch][max_pages_per_seq], values in [0, num_pages) */
+  int32_t *seq_lens;    /* [batch] */
+  int32_t *res_lens;    /* [batch] */
+  int32_t *dev_status;  /* [1] or NULL */
+} oscar_cache;
+
+/* Byte sizes of every pool for `batch` sequences and `num_pages` physical pages. */
+typedef struct oscar_pool_sizes {
+  size_t k_codes, k_meta, k_norms, v_codes, v_meta; /* whole pools */
+  size_t res_k, res_v, res_norm;
+  size_t block_table, seq_lens, res_lens;
+  size_t page_bytes_per_kv_head;  /* packed bytes of one page of one kv head (all five pools) */
+  size_t bytes_per_token_kv_head; /* = page_bytes_per_kv_head / page_size */
+} oscar_pool_sizes;
+
+int oscar_version(void);
+const char *oscar_status_string(int status);
+
+/* Validates cfg and fills *out. Host only. */
+int oscar_cache_sizes(const oscar_config *cfg, int32_t batch, int32_t num_pages,
+                      int32_t max_pages_per_seq, oscar_pool_sizes *out);
+
+/* Number of sequence splits oscar_decode_attn uses when num_splits == 0, for the
+ * device current at the time of the call. Host only; >= 1. */
+int32_t oscar_decode_auto_splits(const oscar_config *cfg, int32_t batch, int32_t max_seq_len);
+
+/* Bytes of split-K scratch oscar_decode_attn needs for `num_splits` splits
+ * (fp32 partial outputs and softmax statistics per batch, query head and split). */
+size_t oscar_decode_workspace_bytes(const oscar_config *cfg, int32_t batch, int32_t num_splits);
+
+/* KV-cache compression: BufferQuantK / BufferQuantV of the algorithm, with the
+ * key transform K_h = H(K)/sqrt(d), n = ||K_h||, K_u = K_h/n fused in front.
+ *   k, v     : device, [batch][T][n_kv_heads][head_dim] contiguous, io_dtype,
+ *              the T newest tokens of every sequence (keys after RoPE, un-rotated)
+ *   new_lens : device int32[batch] or NULL; sequence b appends its first
+ *              new_lens[b] (0..T) tokens; NULL = T for all
+ *   max_seq_len_hint : upper bound on seq_lens[] BEFORE the call, or < 0 if
+ *              unknown; used only for the host-side capacity check
+ *   flags    : OSCAR_APPEND_EAGER = prefill rule (every completed block of R
+ *              tokens is quantized by this call, the tail < R stays 16-bit).
+ *              Default = decode rule: a block completed by this call stays in the
+ *              residual through the attention that follows (the algorithm attends
+ *              before it flushes) and is quantized by the next append.
+ * Updates seq_lens / res_lens on the device. Residual keys are quantized from
+ * their stored fp16 values (no second rotation). */
+int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t *new_lens,
+                          oscar_cache *cache, int32_t max_seq_len_hint, uint32_t flags,
+                          void *stream);
+
+/* Fused decode attention over the packed + residual cache (kernel (iii) of the
+ * paper's system design; OScaR-Inference lines K_all, V_all, Attention):
+ *   out[b][h] = softmax_i( scale * n_i * <Q_h, dequant(K_u,i)> ) . dequant(V_i)
+ * with Q_h = H(q)/sqrt(d) computed inside (pass the UN-rotated query).
+ *   q   : device, [batch][n_q_heads][head_dim], io_dtype
+ *   out : device, [batch][n_q_heads][head_dim], out_dtype (OSCAR_F32 or io_dtype)
+ *   softmax_scale : <= 0 means 1/sqrt(head_dim)
+ *   max_seq_len_hint : upper bound on seq_lens[] (>= 1); sizes the launch
+ *   num_splits : split-K factor over the sequence, 0 = oscar_decode_auto_splits
+ *   workspace  : device scratch of at least oscar_decode_workspace_bytes(...)
+ * A sequence with seq_lens[b] == 0 yields zeros. */
+int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_t out_dtype,
+                      float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* 16-bit comparator: the same split-K decode attention on an uncompressed,
+ * un-rotated cache (the BF16 FlashDecoding-style baseline of the paper's
+ * efficiency section).
+ *   q : device [batch][n_q_heads][d]; k, v : device [batch][kv_stride_tokens][n_kv_heads][d];
+ *   all of `dtype` (OSCAR_BF16 or OSCAR_F16); seq_lens: device int32[batch] (<= kv_stride_tokens);
+ *   out: device [batch][n_q_heads][d] of out_dtype (OSCAR_F32 or dtype);
+ *   workspace as oscar_decode_workspace_bytes for the same head counts. */
+int oscar_bf16_decode_attn(const void *q, const void *k, const void *v, const int32_t *seq_lens,
+                           void *out, int32_t dtype, int32_t out_dtype, int32_t batch,
+                           int32_t kv_stride_tokens, int32_t n_q_heads, int32_t n_kv_heads,
+                           int32_t head_dim, float softmax_scale, int32_t max_seq_len_hint,
+                           int32_t num_splits, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/* Test/debug: copy sequence b, kv head h back to the HOST in a layout-free
+ * form (one code per byte). Synchronizes `stream`. Host outputs, each may be
+ * NULL; `cap_tokens` is the token capacity of the caller's arrays.
+ *   k_codes[cap][d], k_delta/k_zero[cap/k_group][d], k_norm[cap],
+ *   v_codes[cap][d], v_delta/v_zero[cap][d/v_group],
+ *   res_k[R][d], res_v[R][d] (fp32 widened), res_norm[R];
+ *   lens[2] = {seq_len, res_len}. */
+int oscar_debug_dump(const oscar_cache *cache, int32_t b, int32_t h, int32_t cap_tokens,
+                     uint8_t *k_codes, float *k_delta, float *k_zero, float *k_norm,
+                     uint8_t *v_codes, float *v_delta, float *v_zero, float *res_k,
+                     float *res_v, float *res_norm, int32_t *lens, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSCAR_H_ */

@@ -1,0 +1,57 @@
+"""Build the HIP library in-tree for gfx950:  python -m paper_2605_19660_amd.build"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "liboscar_hip.so")
+
+COMMON = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+          # packed fp32 VALU forms are kept out of every device code object
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-Wno-unused-command-line-argument"]
+# per-file extras: the encoder's fp32 operation order is part of the format
+SOURCES = {
+    "oscar_api.hip": [],
+    "oscar_quantize.hip": ["-ffp-contract=off"],
+    "oscar_decode.hip": [],
+    "oscar_decode_mfma.hip": [],
+    "oscar_bf16_decode.hip": [],
+}
+
+
+def _compile(name: str, extra: list[str], verbose: bool) -> str:
+    src = os.path.join(CSRC, name)
+    obj = os.path.join(OBJ, name.replace(".hip", ".o"))
+    cmd = ["hipcc", *COMMON, *extra, "-c", src, "-o", obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {name}:\n{err}")
+    if verbose and err.strip():
+        print(err, flush=True)
+    return obj
+
+
+def build(verbose: bool = False, jobs: int = 4) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    present = {n: e for n, e in SOURCES.items() if os.path.exists(os.path.join(CSRC, n))}
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(lambda kv: _compile(kv[0], kv[1], verbose), present.items()))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose="-q" not in sys.argv))

@@ -1,0 +1,424 @@
+// oscar_decode_attn, generic plain-ALU path: split-K partial pass over the packed
+// pages + the 16-bit residual, then a log-sum-exp reduce pass.
+//
+//   logit[h][i] = scale * n_i * sum_j Q_h[h][j] * Delta_k[g(i)][j] * (c_k[i][j] - z_k[g(i)][j])
+//   out[h][j]   = sum_i softmax(logit[h])_i * Delta_v[i][G(j)] * (c_v[i][j] - z_v[i][G(j)])
+// (App. "Implementation Details ...": logits = (Q_h . dequant(K_u)) * n_k; Algorithm
+// "The OScaR algorithm", lines K_all / V_all / Attention; quantizer of Eq. 3-4.)
+//
+// The scales are folded so the inner loops touch raw integer codes:
+//   A[g][h][j] = Q_h[h][j] * Delta_k[g][j]   and   bias[g][h] = sum_j A[g][h][j] * z_k[g][j]
+// are built once per page, so logit = n_i * (sum_j A * c - bias); on the value side
+// w = Delta_v * c + (-Delta_v * z_v) is one fused multiply-add per element.
+// One workgroup serves all query heads of a kv head, so every packed byte is read once.
+#include "oscar_common.h"
+
+namespace {
+
+constexpr int D = OSCAR_D;
+constexpr int R = OSCAR_R;
+constexpr int WS_STRIDE = D + 2;  // partial record: o[128], m, l
+
+struct DecodeParams {
+  const void* q;
+  void* out;
+  float* ws;
+  oscar_cache c;
+  PageGeom g;
+  int num_splits;
+  float qk_scale_log2;  // softmax scale * log2(e)
+  int out_dtype;
+};
+
+__device__ __forceinline__ float load_io(const void* p, size_t idx, int dt) {
+  if (dt == OSCAR_F32) return reinterpret_cast<const float*>(p)[idx];
+  const uint16_t h = reinterpret_cast<const uint16_t*>(p)[idx];
+  if (dt == OSCAR_BF16) return __uint_as_float((uint32_t)h << 16);
+  return __half2float(__ushort_as_half(h));
+}
+
+__device__ __forceinline__ float load_meta(const void* p, size_t idx, int meta_bytes) {
+  if (meta_bytes == 4) return reinterpret_cast<const float*>(p)[idx];
+  return __half2float(__ushort_as_half(reinterpret_cast<const uint16_t*>(p)[idx]));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+// Q_h = H(q)/sqrt(128) for GQ heads in LDS, times scale*log2(e).
+template <int GQ>
+__device__ __forceinline__ void rotate_queries(float (*s_q)[D], const void* q, size_t q_base,
+                                               int io_dtype, float mul, int tid) {
+  for (int i = tid; i < GQ * D; i += 256) s_q[i / D][i % D] = load_io(q, q_base + i, io_dtype);
+  __syncthreads();
+  for (int h = 1; h < D; h <<= 1) {
+    for (int i = tid; i < GQ * (D / 2); i += 256) {
+      const int head = i / (D / 2), pr = i % (D / 2);
+      const int lo = ((pr & ~(h - 1)) << 1) | (pr & (h - 1));  // index with bit h clear
+      const float a = s_q[head][lo], b = s_q[head][lo | h];
+      s_q[head][lo] = a + b;
+      s_q[head][lo | h] = a - b;
+    }
+    __syncthreads();
+  }
+  const float c = 0.08838834764831845f * mul;
+  for (int i = tid; i < GQ * D; i += 256) s_q[i / D][i % D] *= c;
+  __syncthreads();
+}
+
+template <int BITS, int GQ>
+__global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams P) {
+  constexpr int CPW = 32 / BITS;  // codes per 32-bit word
+  constexpr int KWORDS = 64 / CPW;  // words per half key row (64 channels)
+  constexpr uint32_t CMASK = (1u << BITS) - 1u;
+
+  __shared__ __align__(16) float s_q[GQ][D];
+  __shared__ __align__(16) float s_A[4][GQ][D];
+  __shared__ float s_bias[4][GQ];
+  __shared__ __align__(16) float s_kd[4][D];
+  __shared__ __align__(16) float s_kz[4][D];
+  __shared__ float s_norm[R];
+  __shared__ __align__(16) float2 s_vdz[4][R];  // (Delta_v, -Delta_v * z_v)
+  __shared__ __align__(16) float s_S[GQ][R];
+  __shared__ float s_m[GQ], s_l[GQ], s_alpha[GQ];
+
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
+  const int ngk = P.g.ngk, ngv = P.g.ngv, mb = P.g.meta_bytes;
+
+  const int seq_len = P.c.seq_lens[b];
+  const int r = P.c.res_lens[b];
+  const int n_pages = (seq_len - r) / R;
+  const int pps = (n_pages + P.num_splits - 1) / P.num_splits;
+  const int pg0 = split * pps;
+  const int pg1 = min(n_pages, pg0 + pps);
+  const bool has_res = (split == P.num_splits - 1) && r > 0;
+
+  if (tid < GQ) {
+    s_m[tid] = -INFINITY;
+    s_l[tid] = 0.0f;
+  }
+  float o[GQ];
+#pragma unroll
+  for (int h = 0; h < GQ; ++h) o[h] = 0.0f;
+
+  const bool any_work = (pg0 < pg1) || has_res;
+  if (any_work) {
+    rotate_queries<GQ>(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * GQ) * D, P.c.cfg.io_dtype,
+                       P.qk_scale_log2, tid);
+  } else {
+    __syncthreads();
+  }
+
+  const int tok = tid >> 1, half = tid & 1;  // logit phase: (token, channel half)
+  const int ch = tid >> 1, th = tid & 1;     // value phase: (channel, token half)
+
+  for (int pg = pg0; pg < pg1; ++pg) {
+    const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + pg];
+    const size_t pgi = (size_t)phys * Hkv + kvh;
+    const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(P.c.k_codes) + pgi * P.g.k_codes_bytes;
+    const uint8_t* kmeta = reinterpret_cast<const uint8_t*>(P.c.k_meta) + pgi * P.g.k_meta_bytes;
+    const uint8_t* knorm = reinterpret_cast<const uint8_t*>(P.c.k_norms) + pgi * P.g.k_norms_bytes;
+    const uint8_t* vcodes = reinterpret_cast<const uint8_t*>(P.c.v_codes) + pgi * P.g.v_codes_bytes;
+    const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
+
+    // issue the code loads early
+    uint32_t kw[KWORDS], vw[KWORDS];
+    {
+      const uint4* kp = reinterpret_cast<const uint4*>(kcodes + (size_t)tok * P.g.k_row_bytes + half * (P.g.k_row_bytes / 2));
+      const uint4* vp = reinterpret_cast<const uint4*>(vcodes + (size_t)ch * P.g.v_row_bytes + th * (P.g.v_row_bytes / 2));
+#pragma unroll
+      for (int i = 0; i < KWORDS / 4; ++i) {
+        uint4 a = kp[i], c = vp[i];
+        kw[4 * i] = a.x; kw[4 * i + 1] = a.y; kw[4 * i + 2] = a.z; kw[4 * i + 3] = a.w;
+        vw[4 * i] = c.x; vw[4 * i + 1] = c.y; vw[4 * i + 2] = c.z; vw[4 * i + 3] = c.w;
+      }
+    }
+    // (0) metadata -> LDS as fp32
+    for (int i = tid; i < ngk * D; i += 256) {
+      s_kd[i / D][i % D] = load_meta(kmeta, i, mb);
+      s_kz[i / D][i % D] = load_meta(kmeta, (size_t)ngk * D + i, mb);
+    }
+    if (tid < R) s_norm[tid] = load_meta(knorm, tid, mb);
+    for (int i = tid; i < ngv * R; i += 256) {
+      const float dv = load_meta(vmeta, i, mb);
+      const float zv = load_meta(vmeta, (size_t)ngv * R + i, mb);
+      s_vdz[i / R][i % R] = make_float2(dv, -dv * zv);
+    }
+    __syncthreads();
+    // (1) A = Q_h * Delta_k, bias = sum_j A * z_k ; pair (group, head) -> one wave
+    for (int pr = wave; pr < ngk * GQ; pr += 4) {
+      const int gk = pr / GQ, h = pr % GQ;
+      const float a0 = s_q[h][lane] * s_kd[gk][lane];
+      const float a1 = s_q[h][lane + 64] * s_kd[gk][lane + 64];
+      s_A[gk][h][lane] = a0;
+      s_A[gk][h][lane + 64] = a1;
+      const float part = wave_sum(a0 * s_kz[gk][lane] + a1 * s_kz[gk][lane + 64]);
+      if (lane == 0) s_bias[gk][h] = part;
+    }
+    __syncthreads();
+    // (2) logits
+    {
+      const int gk = tok / P.g.k_group;
+      float acc[GQ];
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) acc[h] = 0.0f;
+#pragma unroll
+      for (int w = 0; w < KWORDS; ++w) {
+#pragma unroll
+        for (int e4 = 0; e4 < CPW; e4 += 4) {
+          const int j = half * 64 + w * CPW + e4;
+          float c[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) c[e] = (float)((kw[w] >> ((e4 + e) * BITS)) & CMASK);
+#pragma unroll
+          for (int h = 0; h < GQ; ++h) {
+            const float4 a = *reinterpret_cast<const float4*>(&s_A[gk][h][j]);
+            acc[h] = fmaf(a.x, c[0], acc[h]);
+            acc[h] = fmaf(a.y, c[1], acc[h]);
+            acc[h] = fmaf(a.z, c[2], acc[h]);
+            acc[h] = fmaf(a.w, c[3], acc[h]);
+          }
+        }
+      }
+      const float nrm = s_norm[tok];
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) {
+        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
+        if (half == 0) s_S[h][tok] = nrm * (tot - s_bias[gk][h]);
+      }
+    }
+    __syncthreads();
+    // (3) online softmax, heads striped over waves
+    for (int h = wave; h < GQ; h += 4) {
+      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
+      const float m_old = s_m[h];
+      const float m_new = fmaxf(m_old, wave_max(fmaxf(s0, s1)));
+      const float alpha = exp2f(m_old - m_new);
+      const float p0 = exp2f(s0 - m_new), p1 = exp2f(s1 - m_new);
+      const float sum = wave_sum(p0 + p1);
+      s_S[h][lane] = p0;
+      s_S[h][lane + 64] = p1;
+      if (lane == 0) {
+        s_m[h] = m_new;
+        s_l[h] = s_l[h] * alpha + sum;
+        s_alpha[h] = alpha;
+      }
+    }
+    __syncthreads();
+    // (4) o += P * V_hat
+    {
+      const int gv = ch / P.g.v_group;
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) o[h] *= s_alpha[h];
+#pragma unroll
+      for (int w = 0; w < KWORDS; ++w) {
+#pragma unroll
+        for (int e4 = 0; e4 < CPW; e4 += 4) {
+          const int t = th * 64 + w * CPW + e4;
+          float wv[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float2 dz = s_vdz[gv][t + e];
+            wv[e] = fmaf(dz.x, (float)((vw[w] >> ((e4 + e) * BITS)) & CMASK), dz.y);
+          }
+#pragma unroll
+          for (int h = 0; h < GQ; ++h) {
+            const float4 p = *reinterpret_cast<const float4*>(&s_S[h][t]);
+            o[h] = fmaf(p.x, wv[0], o[h]);
+            o[h] = fmaf(p.y, wv[1], o[h]);
+            o[h] = fmaf(p.z, wv[2], o[h]);
+            o[h] = fmaf(p.w, wv[3], o[h]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (has_res) {
+    // residual tokens: fp16 K_u times stored norm, values in the input precision
+    const size_t rb = ((size_t)b * Hkv + kvh) * R;
+    const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
+    if (tid < R) s_norm[tid] = tid < r ? load_meta(P.c.res_norm, rb + tid, mb) : 0.0f;
+    __syncthreads();
+    {
+      float acc[GQ];
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) acc[h] = 0.0f;
+      if (tok < r) {
+        const uint4* kp = reinterpret_cast<const uint4*>(rk + (size_t)tok * D + half * 64);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint4 raw = kp[i];
+          const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
+          float kv[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            kv[2 * e] = __half2float(__ushort_as_half((unsigned short)(wds[e] & 0xffffu)));
+            kv[2 * e + 1] = __half2float(__ushort_as_half((unsigned short)(wds[e] >> 16)));
+          }
+          const int j = half * 64 + i * 8;
+#pragma unroll
+          for (int h = 0; h < GQ; ++h) {
+            const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
+            const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
+            acc[h] = fmaf(qa.x, kv[0], acc[h]);
+            acc[h] = fmaf(qa.y, kv[1], acc[h]);
+            acc[h] = fmaf(qa.z, kv[2], acc[h]);
+            acc[h] = fmaf(qa.w, kv[3], acc[h]);
+            acc[h] = fmaf(qb.x, kv[4], acc[h]);
+            acc[h] = fmaf(qb.y, kv[5], acc[h]);
+            acc[h] = fmaf(qb.z, kv[6], acc[h]);
+            acc[h] = fmaf(qb.w, kv[7], acc[h]);
+          }
+        }
+      }
+      const float nrm = s_norm[tok];
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) {
+        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
+        if (half == 0) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
+      }
+    }
+    __syncthreads();
+    for (int h = wave; h < GQ; h += 4) {
+      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
+      const float m_old = s_m[h];
+      const float m_new = fmaxf(m_old, wave_max(fmaxf(s0, s1)));
+      const float alpha = exp2f(m_old - m_new);
+      const float p0 = exp2f(s0 - m_new), p1 = exp2f(s1 - m_new);
+      const float sum = wave_sum(p0 + p1);
+      s_S[h][lane] = p0;
+      s_S[h][lane + 64] = p1;
+      if (lane == 0) {
+        s_m[h] = m_new;
+        s_l[h] = s_l[h] * alpha + sum;
+        s_alpha[h] = alpha;
+      }
+    }
+    __syncthreads();
+    {
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) o[h] *= s_alpha[h];
+      const int t_end = min(r, th * 64 + 64);
+      for (int t = th * 64; t < t_end; ++t) {
+        const float wv = load_io(P.c.res_v, (rb + t) * D + ch, P.c.cfg.io_dtype);
+#pragma unroll
+        for (int h = 0; h < GQ; ++h) o[h] = fmaf(s_S[h][t], wv, o[h]);
+      }
+    }
+    __syncthreads();
+  }
+
+  // partial record per (b, q head, split)
+#pragma unroll
+  for (int h = 0; h < GQ; ++h) {
+    const float tot = o[h] + __shfl_xor(o[h], 1, 64);
+    if (th == 0) {
+      const size_t rec = ((size_t)b * Hq + (size_t)kvh * GQ + h) * P.num_splits + split;
+      P.ws[rec * WS_STRIDE + ch] = tot;
+    }
+  }
+  if (tid < GQ) {
+    const size_t rec = ((size_t)b * Hq + (size_t)kvh * GQ + tid) * P.num_splits + split;
+    P.ws[rec * WS_STRIDE + D] = s_m[tid];
+    P.ws[rec * WS_STRIDE + D + 1] = s_l[tid];
+  }
+}
+
+}  // namespace
+
+// Reduce pass shared with the 16-bit comparator: merges split partials
+// (o_s, m_s, l_s) with M = max m_s, out = sum o_s 2^(m_s-M) / sum l_s 2^(m_s-M).
+__global__ __launch_bounds__(128) void oscar_decode_reduce_kernel(const float* ws, void* out,
+                                                                  int num_splits, int out_dtype) {
+  const size_t unit = (size_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
+  const int c = threadIdx.x;
+  const float* rec = ws + unit * num_splits * WS_STRIDE;
+  float M = -INFINITY;
+  for (int s = 0; s < num_splits; ++s) M = fmaxf(M, rec[(size_t)s * WS_STRIDE + D]);
+  float L = 0.0f, acc = 0.0f;
+  for (int s = 0; s < num_splits; ++s) {
+    const float m = rec[(size_t)s * WS_STRIDE + D];
+    const float w = (m == -INFINITY) ? 0.0f : exp2f(m - M);
+    L += rec[(size_t)s * WS_STRIDE + D + 1] * w;
+    acc += rec[(size_t)s * WS_STRIDE + c] * w;
+  }
+  const float res = L > 0.0f ? acc / L : 0.0f;
+  const size_t oi = unit * D + c;
+  if (out_dtype == OSCAR_F32) reinterpret_cast<float*>(out)[oi] = res;
+  else if (out_dtype == OSCAR_BF16) reinterpret_cast<__hip_bfloat16*>(out)[oi] = __float2bfloat16(res);
+  else reinterpret_cast<__half*>(out)[oi] = __float2half_rn(res);
+}
+
+// Host launcher of the reduce pass (also used by the 16-bit comparator).
+void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int out_dtype,
+                                int n_q_heads, int batch, hipStream_t st) {
+  hipLaunchKernelGGL(oscar_decode_reduce_kernel, dim3(n_q_heads, batch), dim3(128), 0, st, ws, out,
+                     num_splits, out_dtype);
+}
+
+namespace {
+
+template <int BITS>
+int launch_gq(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
+  switch (gq) {
+#define OSCAR_CASE(G) \
+  case G: hipLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st, P); break;
+    OSCAR_CASE(1) OSCAR_CASE(2) OSCAR_CASE(3) OSCAR_CASE(4)
+    OSCAR_CASE(5) OSCAR_CASE(6) OSCAR_CASE(7) OSCAR_CASE(8)
+#undef OSCAR_CASE
+    default: return OSCAR_ERR_UNSUPPORTED;
+  }
+  return OSCAR_OK;
+}
+
+}  // namespace
+
+extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* out,
+                                 int32_t out_dtype, float softmax_scale,
+                                 int32_t max_seq_len_hint, int32_t num_splits, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!cache || !q || !out) return OSCAR_ERR_INVALID_ARG;
+  int rc = oscar_validate_config(&cache->cfg);
+  if (rc != OSCAR_OK) return rc;
+  if (cache->batch <= 0 || cache->max_pages_per_seq <= 0 || max_seq_len_hint < 0 || num_splits < 0)
+    return OSCAR_ERR_INVALID_ARG;
+  if (!cache->k_codes || !cache->k_meta || !cache->k_norms || !cache->v_codes || !cache->v_meta ||
+      !cache->res_k || !cache->res_v || !cache->res_norm || !cache->block_table ||
+      !cache->seq_lens || !cache->res_lens)
+    return OSCAR_ERR_INVALID_ARG;
+  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
+  if (num_splits == 0) num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
+  const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
+  if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
+
+  DecodeParams P;
+  P.q = q;
+  P.out = out;
+  P.ws = reinterpret_cast<float*>(workspace);
+  P.c = *cache;
+  P.g = make_geom(cache->cfg.bits, cache->cfg.k_group, cache->cfg.v_group, cache->cfg.meta_dtype);
+  P.num_splits = num_splits;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 0.08838834764831845f;
+  P.qk_scale_log2 = scale * 1.4426950408889634f;
+  P.out_dtype = out_dtype;
+  const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
+  dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st) : launch_gq<4>(P, gq, grid, st);
+  if (rc != OSCAR_OK) return rc;
+  oscar_launch_decode_reduce(P.ws, out, num_splits, out_dtype, cache->cfg.n_q_heads, cache->batch, st);
+  if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+  return OSCAR_OK;
+}

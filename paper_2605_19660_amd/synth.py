@@ -166,3 +166,28 @@ def cache_bytes_per_token_kvh(w: Workload) -> int:
     k_meta = 2 * meta * d // w.k_group
     v_meta = 2 * meta * d // w.v_group
     return codes + k_meta + meta + codes + v_meta
+
+
+def make_kv_device(w: Workload, device="cuda", b_range=None):
+    """Full-size K, V on the GPU: torch tensors [batch, context, n_kv_heads, d] of the
+    workload's io dtype.  Same recipe as make_kv (base N(0,1), outlier channels, per-token
+    multipliers) but drawn with torch's seeded device generator so that hundreds of
+    megabytes need not cross PCIe; a slice copied back to the host feeds the oracle."""
+    import torch
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[w.io_dtype]
+    bs = range(w.batch) if b_range is None else b_range
+    ch = torch.from_numpy(outlier_channel_table(w)).to(device)
+    gain = torch.ones(w.n_kv_heads, w.head_dim, device=device)
+    gain.scatter_(1, ch, float(w.outlier_gain))
+    ks, vs = [], []
+    for b in bs:
+        gen = torch.Generator(device=device)
+        gen.manual_seed(w.seed * 1000 + b)
+        m = torch.from_numpy(token_multipliers(w, b, 0, w.context)).to(device)
+        scale = m[:, None, None] * gain[None]
+        k = torch.randn(w.context, w.n_kv_heads, w.head_dim, device=device, generator=gen)
+        ks.append((k * scale).to(dt))
+        v = torch.randn(w.context, w.n_kv_heads, w.head_dim, device=device, generator=gen)
+        vs.append((v * scale).to(dt))
+        del k, v
+    return torch.stack(ks), torch.stack(vs)

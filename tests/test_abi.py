@@ -1,0 +1,72 @@
+"""The C-ABI library loads, exports every symbol the header declares, and its
+host-only entry points behave (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_19660_amd import binding as ob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "oscar.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(oscar_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    L = ob.lib()
+    names = declared_symbols()
+    assert set(names) == set(ob.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings():
+    assert ob.lib().oscar_version() == 100
+    assert ob.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert ob.status_string(code) not in ("ok", "unknown status")
+
+
+def test_cache_sizes_match_the_format():
+    cfg = ob.Config(32, 8)                     # INT2, G_k=128, G_v=32, fp16 metadata
+    sz = ob.cache_sizes(cfg, 8, 16, 4)
+    assert sz.page_bytes_per_kv_head == 11008 and sz.bytes_per_token_kv_head == 86
+    assert sz.k_codes == 16 * 8 * 4096 and sz.v_meta == 16 * 8 * 2048
+    assert sz.res_k == 8 * 8 * 128 * 128 * 2
+    assert ob.cache_sizes(ob.Config(32, 8, bits=4), 1, 1, 1).bytes_per_token_kv_head == 150
+    assert ob.cache_sizes(ob.Config(32, 8, k_group=32), 1, 1, 1).bytes_per_token_kv_head == 98
+    assert ob.cache_sizes(ob.Config(1, 1, io_dtype=ob.F32, meta_dtype=ob.F32), 1, 1, 1).bytes_per_token_kv_head == 108
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=64), ob.ERR_UNSUPPORTED),
+    (dict(bits=3), ob.ERR_UNSUPPORTED),
+    (dict(bits=0), ob.ERR_INVALID_ARG),
+    (dict(k_group=48), ob.ERR_INVALID_ARG),
+    (dict(k_group=16), ob.ERR_UNSUPPORTED),
+    (dict(zp_mode=ob.ZP_MIN), ob.ERR_UNSUPPORTED),
+    (dict(norm_scope=ob.NORM_ALL_KV_HEADS), ob.ERR_UNSUPPORTED),
+    (dict(n_q_heads=30), ob.ERR_INVALID_ARG),
+    (dict(n_q_heads=128), ob.ERR_UNSUPPORTED),
+    (dict(io_dtype=7), ob.ERR_INVALID_ARG),
+])
+def test_config_validation(kw, code):
+    base = dict(n_q_heads=32, n_kv_heads=8)
+    base.update(kw)
+    with pytest.raises(ob.OscarError) as e:
+        ob.cache_sizes(ob.Config(**base), 1, 1, 1)
+    assert e.value.status == code
+
+
+def test_null_arguments_are_rejected_before_any_launch():
+    L = ob.lib()
+    assert L.oscar_quantize_append(None, None, 1, None, None, -1, 0, None) == ob.ERR_INVALID_ARG
+    assert L.oscar_decode_attn(None, None, None, 0, 0.0, 1, 1, None, 0, None) == ob.ERR_INVALID_ARG
+    cc = ob.Config(32, 8).c()
+    assert L.oscar_cache_sizes(C.byref(cc), 1, 1, 1, None) == ob.ERR_INVALID_ARG
+    assert ob.decode_workspace_bytes(ob.Config(32, 8), 8, 16) == 8 * 32 * 16 * 130 * 4

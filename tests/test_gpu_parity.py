@@ -1,0 +1,287 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same
+seeded inputs.  Encoder outputs (codes, Delta, zero-points, norms, residual) must be
+bit-exact; decode outputs within rel-L2 <= 1e-3 and max-abs <= 5e-3 of the oracle on
+the same cache."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleCache, OracleConfig
+from paper_2605_19660_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-3
+MAX_ABS = 5e-3
+
+DT = {"f32": 0, "bf16": 1, "f16": 2}
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ob():
+    from paper_2605_19660_amd import binding
+    return binding
+
+
+def to_dev(x, io):
+    torch = _torch()
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[io]
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dt).contiguous()
+
+
+def make_pair(w: synth.Workload, cap_pages, page_perm=None):
+    ob = _ob()
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
+                    w.page_size, DT[w.io_dtype], DT[w.meta_dtype])
+    g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm)
+    o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
+                                 DT[w.meta_dtype]), w.batch, w.n_kv_heads, (cap_pages + 1) * w.page_size)
+    return g, o
+
+
+def assert_cache_equal(g, o, w):
+    ob = _ob()
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            d = ob.debug_dump(g, b, h)
+            npk, nr = int(o.n_packed[b]), int(o.n_res[b])
+            assert (int(d["lens"][0]), int(d["lens"][1])) == (npk + nr, nr), (b, h, d["lens"], npk, nr)
+            ngk = npk // w.k_group
+            for name, got, want in (
+                    ("k_codes", d["k_codes"][:npk], o.k_codes[b, h, :npk]),
+                    ("v_codes", d["v_codes"][:npk], o.v_codes[b, h, :npk]),
+                    ("k_delta", d["k_delta"][:ngk], o.k_delta[b, h, :ngk]),
+                    ("k_zero", d["k_zero"][:ngk], o.k_zero[b, h, :ngk]),
+                    ("k_norm", d["k_norm"][:npk], o.k_norm[b, h, :npk]),
+                    ("v_delta", d["v_delta"][:npk], o.v_delta[b, h, :npk]),
+                    ("v_zero", d["v_zero"][:npk], o.v_zero[b, h, :npk]),
+                    ("res_k", d["res_k"][:nr], o.res_k[b, h, :nr]),
+                    ("res_v", d["res_v"][:nr], o.res_v[b, h, :nr]),
+                    ("res_norm", d["res_norm"][:nr], o.res_norm[b, h, :nr])):
+                if not np.array_equal(got, want):
+                    bad = np.argwhere(got != want)
+                    raise AssertionError(f"{name} differs at (b={b},h={h}): {len(bad)} of {got.size}; "
+                                         f"first {bad[0]} got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}")
+
+
+def assert_decode_close(got, want):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+    mx = np.abs(got - want).max()
+    assert rel <= REL_L2 and mx <= MAX_ABS, (rel, mx)
+
+
+# ------------------------------------------------------------------ encoder --
+
+def test_tiny_config_bitexact_encoder_and_decode():
+    w = synth.TINY
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8)
+    ob = _ob()
+    ob.quantize_append(g, to_dev(k, w.io_dtype), to_dev(v, w.io_dtype), eager=True, max_seq_len_hint=0)
+    o.append(k, v, eager=True)
+    assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
+@pytest.mark.parametrize("io,meta,bits,kg,vg", [
+    ("bf16", "f16", 2, 128, 32),
+    ("bf16", "f16", 4, 128, 32),
+    ("bf16", "f16", 2, 32, 32),
+    ("f16", "f16", 2, 64, 64),
+    ("bf16", "f32", 4, 32, 128),
+    ("f32", "f16", 2, 128, 128),
+])
+def test_prefill_bitexact_ragged(io, meta, bits, kg, vg):
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 5 + 37,
+                                  io_dtype=io, meta_dtype=meta, bits=bits, k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8)
+    ob = _ob()
+    ob.quantize_append(g, to_dev(k, io), to_dev(v, io), eager=True, max_seq_len_hint=0)
+    o.append(k, v, eager=True)
+    assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
+def test_incremental_appends_deferred_flush_and_ragged_new_lens():
+    """Mixed chunk sizes, per-sequence new_lens, flush of a full residual deferred to the
+    next append (the block stays 16-bit through the attention in between)."""
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=3, n_q_heads=12, n_kv_heads=3, context=700)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 8)
+    pos = np.zeros(w.batch, np.int64)
+    steps = [(100, [100, 60, 0]), (28, [28, 28, 28]), (1, [1, 1, 1]), (130, [130, 40, 129]),
+             (1, [0, 1, 1]), (256, [256, 200, 1]), (1, [1, 1, 1])]
+    step_id = 0
+    for T, lens in steps:
+        kk = np.zeros((w.batch, T, w.n_kv_heads, w.head_dim), np.float32)
+        vv = np.zeros_like(kk)
+        for b in range(w.batch):
+            kk[b, :lens[b]] = k[b, pos[b]:pos[b] + lens[b]]
+            vv[b, :lens[b]] = v[b, pos[b]:pos[b] + lens[b]]
+        nl = np.asarray(lens, np.int32)
+        ob.quantize_append(g, to_dev(kk, w.io_dtype), to_dev(vv, w.io_dtype),
+                           new_lens=torch.from_numpy(nl).cuda())
+        o.append(kk, vv, new_lens=nl)
+        pos += nl
+        assert_cache_equal(g, o, w)
+        q = synth.make_q(w, step_id)
+        out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=int(pos.max()))
+        assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+        step_id += 1
+    assert int(g.dev_status.item()) == 0
+
+
+def test_token_by_token_equals_bulk_on_gpu():
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=1, n_q_heads=4, n_kv_heads=1, context=300)
+    k, v = synth.make_kv_batch(w)
+    ga, o = make_pair(w, 4)
+    gb, _ = make_pair(w, 4)
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    ob.quantize_append(ga, kd, vd)                       # one deferred bulk call
+    for t in range(w.context):
+        ob.quantize_append(gb, kd[:, t:t + 1].contiguous(), vd[:, t:t + 1].contiguous())
+    o.append(k, v)
+    assert_cache_equal(ga, o, w)
+    assert_cache_equal(gb, o, w)
+
+
+# ------------------------------------------------------------------- decode --
+
+@pytest.mark.parametrize("hq,hkv,bits", [(1, 1, 2), (8, 2, 2), (28, 4, 2), (16, 2, 4), (6, 2, 4)])
+def test_decode_gqa_variants_split_and_page_permutation_invariance(hq, hkv, bits):
+    ob = _ob()
+    w = synth.OMNI_64K.replace(batch=2, n_q_heads=hq, n_kv_heads=hkv, context=128 * 9 + 77,
+                               bits=bits, segment_len=(100, 400))
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    rng = np.random.default_rng(3)
+    perm = rng.permutation(2 * 12)
+    g, o = make_pair(w, 12)
+    gp, _ = make_pair(w, 12, page_perm=perm)
+    kd, vd, qd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype), to_dev(q, w.io_dtype)
+    ob.quantize_append(g, kd, vd, eager=True)
+    ob.quantize_append(gp, kd, vd, eager=True)
+    o.append(k, v, eager=True)
+    want = o.decode_attn(q)
+    outs = []
+    for splits in (1, 2, 3, 5, 16):
+        out = ob.decode_attn(g, qd, max_seq_len_hint=w.context, num_splits=splits).cpu().numpy()
+        assert_decode_close(out, want)
+        outs.append(out)
+    for a in outs[1:]:
+        assert np.abs(a - outs[0]).max() <= 2e-5 * max(1.0, np.abs(outs[0]).max())
+    outp = ob.decode_attn(gp, qd, max_seq_len_hint=w.context, num_splits=3).cpu().numpy()
+    assert np.array_equal(outp, outs[2])
+    # a bf16 output buffer is the rounded fp32 result
+    import torch
+    ob16 = ob.decode_attn(g, qd, out=torch.empty_like(qd), max_seq_len_hint=w.context, num_splits=3)
+    assert torch.equal(ob16.float().cpu(), torch.from_numpy(outs[2]).to(torch.bfloat16).float())
+
+
+def test_decode_edge_cases_empty_residual_only_and_exact_pages():
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=4, n_q_heads=8, n_kv_heads=2, context=256)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 4)
+    lens = np.asarray([0, 5, 256, 128], np.int32)    # empty, residual only, two full pages, one page
+    ob.quantize_append(g, to_dev(k, w.io_dtype), to_dev(v, w.io_dtype),
+                       new_lens=torch.from_numpy(lens).cuda(), eager=True)
+    o.append(k, v, new_lens=lens, eager=True)
+    assert_cache_equal(g, o, w)
+    want = o.decode_attn(q)
+    assert not want[0].any()
+    for splits in (1, 4):
+        out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=256, num_splits=splits).cpu().numpy()
+        assert_decode_close(out, want)
+        assert not out[0].any()
+
+
+def test_capacity_and_argument_errors():
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=1, n_q_heads=4, n_kv_heads=1, context=400)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 2)                            # room for 2 pages + residual
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    with pytest.raises(ob.OscarError) as e:           # host-side check through the hint
+        ob.quantize_append(g, kd, vd, eager=True, max_seq_len_hint=0)
+    assert e.value.status == ob.ERR_CAPACITY
+    ob.quantize_append(g, kd, vd, eager=True)         # no hint: the device guard drops it
+    torch.cuda.synchronize()
+    assert int(g.dev_status.item()) == ob.ERR_CAPACITY and int(g.seq_lens.item()) == 0
+    ob.quantize_append(g, kd[:, :300].contiguous(), vd[:, :300].contiguous(), eager=True)
+    o.append(k[:, :300], v[:, :300], eager=True)
+    assert_cache_equal(g, o, w)
+    q = to_dev(synth.make_q(w), w.io_dtype)
+    with pytest.raises(ob.OscarError) as e:
+        ob.decode_attn(g, q, max_seq_len_hint=300, num_splits=4,
+                       workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == ob.ERR_WORKSPACE
+
+
+# -------------------------------------------------------------- comparator --
+
+@pytest.mark.parametrize("io", ["bf16", "f16"])
+def test_bf16_comparator_matches_plain_attention_oracle(io):
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=3, n_q_heads=8, n_kv_heads=2, context=1000, io_dtype=io)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    lens = np.asarray([1000, 1, 517], np.int32)
+    want = oracle.plain_attn(q, k, v, seq_lens=lens)
+    for splits in (1, 7):
+        out = ob.bf16_decode_attn(to_dev(q, io), to_dev(k, io), to_dev(v, io),
+                                  torch.from_numpy(lens).cuda(), num_splits=splits).cpu().numpy()
+        assert_decode_close(out, want)
+
+
+# ------------------------------------------------- full size, sampled check --
+
+def test_full_size_config1_sampled_against_oracle():
+    """Llama-3-8B-like decode at its full size in the launch configuration the benchmark
+    times: every encoder output of sampled (sequence, kv head) streams bit-exact, decode
+    outputs of their query heads within tolerance."""
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K
+    kd, vd = synth.make_kv_device(w)
+    qh = synth.make_q(w)
+    pages = w.context // w.page_size + 1
+    g, _ = make_pair(w.replace(batch=w.batch), pages)
+    ob.quantize_append(g, kd, vd, eager=True, max_seq_len_hint=0)
+    out = ob.decode_attn(g, to_dev(qh, w.io_dtype), max_seq_len_hint=w.context).cpu().numpy()
+    gq = w.n_q_heads // w.n_kv_heads
+    for (b, h) in ((0, 0), (3, 5), (7, 7)):
+        ks = kd[b, :, h].float().cpu().numpy()[None, :, None, :]
+        vs = vd[b, :, h].float().cpu().numpy()[None, :, None, :]
+        o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
+                                     DT[w.meta_dtype]), 1, 1, pages * w.page_size)
+        o.append(ks, vs, eager=True)
+        d = ob.debug_dump(g, b, h)
+        npk = int(o.n_packed[0])
+        assert np.array_equal(d["k_codes"][:npk], o.k_codes[0, 0, :npk])
+        assert np.array_equal(d["v_codes"][:npk], o.v_codes[0, 0, :npk])
+        assert np.array_equal(d["k_delta"][:npk // w.k_group], o.k_delta[0, 0, :npk // w.k_group])
+        assert np.array_equal(d["k_zero"][:npk // w.k_group], o.k_zero[0, 0, :npk // w.k_group])
+        assert np.array_equal(d["k_norm"][:npk], o.k_norm[0, 0, :npk])
+        assert np.array_equal(d["v_delta"][:npk], o.v_delta[0, 0, :npk])
+        assert np.array_equal(d["v_zero"][:npk], o.v_zero[0, 0, :npk])
+        want = o.decode_attn(qh[b:b + 1, h * gq:(h + 1) * gq], nthreads=4)
+        assert_decode_close(out[b, h * gq:(h + 1) * gq], want[0])

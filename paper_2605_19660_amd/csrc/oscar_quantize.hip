@@ -77,6 +77,14 @@ __device__ __forceinline__ void copy8<__hip_bfloat16>(__hip_bfloat16* dst,
   *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
+// Keeps a value in a VGPR across an empty asm: stops the compiler from folding the
+// fp32 multiply and the fp16 conversion below into one mixed-precision instruction that
+// rounds the exact product once (the format rounds to fp32 first, then to fp16).
+__device__ __forceinline__ float pin_f32(float x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 __device__ __forceinline__ uint32_t half_bits(float x) {
   return (uint32_t)__half_as_ushort(__float2half_rn(x));
 }
@@ -121,7 +129,7 @@ __device__ __forceinline__ void key_transform8(float (&x)[8], int sub, float& n_
   float nf = round_meta<META>(n);
   float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = __half2float(__float2half_rn(x[i] * inv));
+  for (int i = 0; i < 8; ++i) x[i] = __half2float(__float2half_rn(pin_f32(x[i] * inv)));
   n_st = nf;
 }
 

@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the OScaR hot path on one MI355X.
+
+One "step" = one decode step of the whole hot path over the workload's batch:
+  oscar_quantize_append of 1 new token per sequence (rotation, token scaling, residual
+  append, block flush when due)  +  oscar_decode_attn over the packed + residual cache
+  (query rotation, split-K partial pass, reduce pass).
+The compressed cache was built beforehand by a timed oscar_quantize_append prefill of the
+whole context, which is reported separately.  Everything is resident in HBM before the
+timed region.  To keep the numbers HBM numbers and not Infinity-Cache numbers the steps
+rotate over several independent cache copies (think: layers) whose total footprint exceeds
+twice the 256 MB last-level cache.
+
+Prints ONE JSON line (see the design doc for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+LLC_BYTES = 256 << 20       # Infinity Cache
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1, help="index into the five configurations")
+    ap.add_argument("--bits", type=int, default=0, help="override bits (2|4)")
+    ap.add_argument("--splits", type=int, default=0, help="override the split-K factor")
+    ap.add_argument("--copies", type=int, default=0, help="override the number of cache copies")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, kd, vd, q_host, ob_cfg, budget_s=12.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: prefill-encode
+    the sampled sequences, then time decode steps (append one token + attention) for about
+    `budget_s` seconds."""
+    import oracle
+    nb = min(w.batch, 4)
+    threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1, 16))
+    k = kd[:nb].float().cpu().numpy()
+    v = vd[:nb].float().cpu().numpy()
+    meta = {"f16": oracle.F16, "f32": oracle.F32}[w.meta_dtype]
+    cache = oracle.OracleCache(oracle.OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group,
+                                                   w.page_size, meta), nb, w.n_kv_heads,
+                               (w.context // w.page_size + 2) * w.page_size)
+    t0 = time.perf_counter()
+    cache.append(k, v, eager=True, nthreads=threads)
+    t_enc = time.perf_counter() - t0
+    n_steps, t_steps = 0, 0.0
+    while n_steps < 64 and (n_steps == 0 or t_steps + t_steps / n_steps < budget_s):
+        knew, vnew = k[:, n_steps:n_steps + 1].copy(), v[:, n_steps:n_steps + 1].copy()
+        t0 = time.perf_counter()
+        cache.append(knew, vnew, nthreads=threads)
+        cache.decode_attn(q_host[:nb], nthreads=threads)
+        t_steps += time.perf_counter() - t0
+        n_steps += 1
+    t_step = t_steps / n_steps
+    scale = w.batch / nb
+    return {
+        "value": t_step * scale * 1e6, "unit": "us/step", "cores": threads, "kind": "oracle",
+        "sample": f"{nb} of {w.batch} sequences x all {w.n_kv_heads} kv heads x full {w.context} "
+                  f"context; {n_steps} decode steps timed ({t_step:.3f} s each) and scaled x{scale:g}; "
+                  f"prefill encode of the sample took {t_enc:.2f} s "
+                  f"({nb * w.context * w.n_kv_heads / t_enc / 1e6:.2f} M token-heads/s)",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2605_19660_amd import binding as ob, synth
+
+    torch.cuda.set_device(0)
+    w = synth.CONFIGS[args.workload]
+    if args.bits:
+        w = w.replace(bits=args.bits)
+    io = {"f32": ob.F32, "bf16": ob.BF16, "f16": ob.F16}[w.io_dtype]
+    meta = {"f32": ob.F32, "f16": ob.F16}[w.meta_dtype]
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
+                    w.page_size, io, meta)
+    R = w.page_size
+    total_steps = args.steps + args.warmup
+    pages = (w.context + total_steps) // R + 2
+    stream = torch.cuda.current_stream()
+
+    kd, vd = synth.make_kv_device(w)
+    bytes_tok = synth.cache_bytes_per_token_kvh(w)
+    units = w.batch * w.n_kv_heads * (w.context // R) * R      # packed token-heads read per step
+    cache_bytes = units * bytes_tok
+    n_copies = args.copies or max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1)
+
+    # ---- prefill: quantize_append of the whole context, timed per copy ----
+    caches, t_pre = [], []
+    for _ in range(n_copies):
+        c = ob.Cache(cfg, w.batch, pages)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t_pre.append(e0.elapsed_time(e1) * 1e3)
+        caches.append(c)
+    assert all(int(c.dev_status.item()) == 0 for c in caches)
+    pre_us = float(np.median(t_pre))
+    el = 2 if w.io_dtype != "f32" else 4
+    pre_units = w.batch * w.n_kv_heads * w.context
+    pre_bytes = pre_units * (2 * w.head_dim * el) + units * bytes_tok
+
+    # ---- per-step inputs ----
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 77)
+    dt = ob.torch_dtype(io)
+    new_k = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    new_v = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    q_host = synth.make_q(w)
+    q = torch.from_numpy(q_host).cuda().to(dt).contiguous()
+    out = torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    splits = args.splits or ob.decode_auto_splits(cfg, w.batch, w.context + total_steps)
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+
+    def step(i, ev=None):
+        c = caches[i % n_copies]
+        ob.quantize_append(c, new_k[i], new_v[i], stream=stream)
+        if ev is not None:
+            ev[0].record(stream)
+        ob.decode_attn_partial(c, q, ws, splits, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_step = wall / args.steps * 1e6
+    k_us = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e3
+    assert all(int(c.dev_status.item()) == 0 for c in caches)
+    achieved = cache_bytes / (k_us * 1e-6) / 1e9
+
+    # ---- BF16 comparator on the same logical K, V (its 1 GB+ stream is already cold) ----
+    bf16 = None
+    if not args.no_bf16 and w.io_dtype in ("bf16", "f16"):
+        lens = torch.full((w.batch,), w.context, dtype=torch.int32, device="cuda")
+        bsplits = ob.decode_auto_splits(cfg, w.batch, w.context)
+        bws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, bsplits), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            ob.bf16_decode_attn(q, kd, vd, lens, out=out, num_splits=bsplits, workspace=bws, stream=stream)
+        n_rep = max(5, min(50, args.steps // 4))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(n_rep):
+            ob.bf16_decode_attn(q, kd, vd, lens, out=out, num_splits=bsplits, workspace=bws, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        b_us = e0.elapsed_time(e1) * 1e3 / n_rep
+        b_bytes = w.batch * w.n_kv_heads * w.context * 2 * w.head_dim * 2
+        bf16 = {"us_per_step": b_us, "hbm_gbs": b_bytes / (b_us * 1e-6) / 1e9, "splits": bsplits}
+
+    res = {
+        "metric": "int%d_decode_attn_us_per_step" % w.bits,
+        "value": us_step, "unit": "us/step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": us_step / 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u%d codes, f32 accumulate" % w.bits,
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads,
+                   "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "context": w.context,
+                   "bits": w.bits, "k_group": w.k_group, "v_group": w.v_group,
+                   "io_dtype": w.io_dtype, "step": "append 1 token/seq + decode attention",
+                   "splits": splits, "cache_copies_rotated": n_copies},
+        "roofline": {"bound": "hbm", "kernel": "oscar_decode_partial_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": cache_bytes,
+                     "avg_kernel_us": k_us},
+        "decode_tokens_per_s": w.batch / (us_step * 1e-6),
+        "cache_bytes_per_token_kv_head": bytes_tok,
+        "cache_bytes_per_token_all_heads": bytes_tok * w.n_kv_heads,
+        "resident_cache_bytes": cache_bytes,
+        "compression_vs_16bit": 2 * w.head_dim * 2 / bytes_tok,
+        "quantize_append_prefill": {"tokens": w.batch * w.context, "us": pre_us,
+                                    "hbm_gbs": pre_bytes / (pre_us * 1e-6) / 1e9,
+                                    "frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                    "algorithmic_bytes": pre_bytes},
+    }
+    if bf16:
+        res["bf16_decode"] = bf16
+        res["speedup_vs_bf16_decode"] = bf16["us_per_step"] / us_step
+        res["kernel_speedup_vs_bf16_decode"] = bf16["us_per_step"] / k_us
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, kd, vd, q_host, cfg)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

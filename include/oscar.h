@@ -174,6 +174,19 @@ int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_
                       float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* The two passes of oscar_decode_attn as separate calls, for callers that want to time
+ * or overlap them: oscar_decode_attn(...) == partial(...) followed by reduce(...) on the
+ * same stream with the same num_splits (> 0 here) and workspace.
+ * (Split-K partial pass: per (sequence, kv head, split) online-softmax attention over a
+ * range of pages, all query heads of the group sharing each packed tile; reduce pass:
+ * log-sum-exp merge of the splits.) */
+int oscar_decode_attn_partial(const void *q, const oscar_cache *cache, float softmax_scale,
+                              int32_t num_splits, void *workspace, size_t workspace_bytes,
+                              void *stream);
+int oscar_decode_attn_reduce(const oscar_cache *cache, void *out, int32_t out_dtype,
+                             int32_t num_splits, const void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 /* 16-bit comparator: the same split-K decode attention on an uncompressed,
  * un-rotated cache (the BF16 FlashDecoding-style baseline of the paper's
  * efficiency section).

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(_HERE, "liboscar_hip.so")
 
 EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_auto_splits", "oscar_decode_workspace_bytes", "oscar_quantize_append",
-           "oscar_decode_attn", "oscar_bf16_decode_attn", "oscar_debug_dump")
+           "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
+           "oscar_bf16_decode_attn", "oscar_debug_dump")
 
 
 class OscarError(RuntimeError):
@@ -80,6 +81,10 @@ def lib():
     L.oscar_quantize_append.argtypes = [vp, vp, i32, vp, C.POINTER(CCache), i32, u32, vp]
     L.oscar_decode_attn.restype = C.c_int
     L.oscar_decode_attn.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp, sz, vp]
+    L.oscar_decode_attn_partial.restype = C.c_int
+    L.oscar_decode_attn_partial.argtypes = [vp, C.POINTER(CCache), f32, i32, vp, sz, vp]
+    L.oscar_decode_attn_reduce.restype = C.c_int
+    L.oscar_decode_attn_reduce.argtypes = [C.POINTER(CCache), vp, i32, i32, vp, sz, vp]
     L.oscar_bf16_decode_attn.restype = C.c_int
     L.oscar_bf16_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                          f32, i32, i32, vp, sz, vp]
@@ -227,6 +232,24 @@ def decode_attn(cache: Cache, q, out=None, scale: float = 0.0, max_seq_len_hint:
                                  dtype_code(out.dtype), scale, max_seq_len_hint, num_splits,
                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(rc, "oscar_decode_attn")
+    return out
+
+
+def decode_attn_partial(cache: Cache, q, workspace, num_splits: int, scale: float = 0.0,
+                        stream=None):
+    """oscar_decode_attn_partial: first pass only (writes split partials to `workspace`)."""
+    rc = lib().oscar_decode_attn_partial(q.data_ptr(), C.byref(cache.c), scale, num_splits,
+                                         workspace.data_ptr(), workspace.numel(),
+                                         _stream_ptr(stream))
+    _check(rc, "oscar_decode_attn_partial")
+
+
+def decode_attn_reduce(cache: Cache, out, workspace, num_splits: int, stream=None):
+    """oscar_decode_attn_reduce: merge the split partials in `workspace` into `out`."""
+    rc = lib().oscar_decode_attn_reduce(C.byref(cache.c), out.data_ptr(), dtype_code(out.dtype),
+                                        num_splits, workspace.data_ptr(), workspace.numel(),
+                                        _stream_ptr(stream))
+    _check(rc, "oscar_decode_attn_reduce")
     return out
 
 

@@ -385,40 +385,74 @@ int launch_gq(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
 
 }  // namespace
 
-extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* out,
-                                 int32_t out_dtype, float softmax_scale,
-                                 int32_t max_seq_len_hint, int32_t num_splits, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
-  if (!cache || !q || !out) return OSCAR_ERR_INVALID_ARG;
+static int check_decode_cache(const oscar_cache* cache) {
+  if (!cache) return OSCAR_ERR_INVALID_ARG;
   int rc = oscar_validate_config(&cache->cfg);
   if (rc != OSCAR_OK) return rc;
-  if (cache->batch <= 0 || cache->max_pages_per_seq <= 0 || max_seq_len_hint < 0 || num_splits < 0)
-    return OSCAR_ERR_INVALID_ARG;
+  if (cache->batch <= 0 || cache->max_pages_per_seq <= 0) return OSCAR_ERR_INVALID_ARG;
   if (!cache->k_codes || !cache->k_meta || !cache->k_norms || !cache->v_codes || !cache->v_meta ||
       !cache->res_k || !cache->res_v || !cache->res_norm || !cache->block_table ||
       !cache->seq_lens || !cache->res_lens)
     return OSCAR_ERR_INVALID_ARG;
-  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
-  if (num_splits == 0) num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache,
+                                         float softmax_scale, int32_t num_splits,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_decode_cache(cache);
+  if (rc != OSCAR_OK) return rc;
+  if (!q || num_splits <= 0) return OSCAR_ERR_INVALID_ARG;
   const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
-
   DecodeParams P;
   P.q = q;
-  P.out = out;
+  P.out = nullptr;
   P.ws = reinterpret_cast<float*>(workspace);
   P.c = *cache;
   P.g = make_geom(cache->cfg.bits, cache->cfg.k_group, cache->cfg.v_group, cache->cfg.meta_dtype);
   P.num_splits = num_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 0.08838834764831845f;
   P.qk_scale_log2 = scale * 1.4426950408889634f;
-  P.out_dtype = out_dtype;
+  P.out_dtype = OSCAR_F32;
   const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
   dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st) : launch_gq<4>(P, gq, grid, st);
   if (rc != OSCAR_OK) return rc;
-  oscar_launch_decode_reduce(P.ws, out, num_splits, out_dtype, cache->cfg.n_q_heads, cache->batch, st);
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
   return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn_reduce(const oscar_cache* cache, void* out, int32_t out_dtype,
+                                        int32_t num_splits, const void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  int rc = check_decode_cache(cache);
+  if (rc != OSCAR_OK) return rc;
+  if (!out || num_splits <= 0) return OSCAR_ERR_INVALID_ARG;
+  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
+  const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
+  if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
+  oscar_launch_decode_reduce(reinterpret_cast<const float*>(workspace), out, num_splits, out_dtype,
+                             cache->cfg.n_q_heads, cache->batch,
+                             reinterpret_cast<hipStream_t>(stream));
+  if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* out,
+                                 int32_t out_dtype, float softmax_scale,
+                                 int32_t max_seq_len_hint, int32_t num_splits, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  int rc = check_decode_cache(cache);
+  if (rc != OSCAR_OK) return rc;
+  if (!q || !out || max_seq_len_hint < 0 || num_splits < 0) return OSCAR_ERR_INVALID_ARG;
+  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
+  if (num_splits == 0)
+    num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
+  rc = oscar_decode_attn_partial(q, cache, softmax_scale, num_splits, workspace, workspace_bytes,
+                                 stream);
+  if (rc != OSCAR_OK) return rc;
+  return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
+                                  stream);
 }

@@ -86,12 +86,22 @@ typedef struct oscar_config {
  *
  * Packed part: logical page p of sequence b is physical page block_table[b][p];
  * a physical page holds R tokens of ALL kv heads; pools are indexed
- * [physical page][kv head][bytes]:
- *   k_codes : R rows (tokens) of head_dim*bits/8 bytes, channel j at bit j*bits (little endian)
- *   k_meta  : Delta[R/k_group][head_dim] then zero[R/k_group][head_dim]      (meta_dtype)
- *   k_norms : n[R]                                                           (meta_dtype)
- *   v_codes : head_dim rows (channels) of R*bits/8 bytes, token t at bit t*bits
- *   v_meta  : Delta[head_dim/v_group][R] then zero[head_dim/v_group][R]      (meta_dtype)
+ * [physical page][kv head][bytes]. Inside a page the bytes are ordered for the
+ * matrix-core decode kernel (a 64-lane wave loads a 16 x 32-code operand tile as one
+ * contiguous block and each lane's codes are already in operand order); use
+ * oscar_debug_dump to read a cache in plain [token][channel] form.
+ *   k_codes : 8 tiles of 16 tokens; lane (n = t%16, q4) owns the "chunk" of channels
+ *             32*q4..32*q4+31 of token 16*tile+n, code of channel 32*q4+u at bit u*bits;
+ *             tiles are stored in pairs: chunk (tile, n, q4) starts at byte
+ *             ((tile/2)*64 + n*4 + q4) * 8*bits + (tile%2) * 4*bits
+ *   v_codes : same structure with 8 tiles of 16 channels; chunk q4 holds the 32 tokens
+ *             with t%4 == q4, token 16*e + 4*kk + q4 at code number
+ *             slot(kk, e) = 16*(kk/2)+4*(kk%2)+e/2+8*(e%2) (2-bit), 8*kk+e/2+4*(e%2) (4-bit)
+ *   k_meta  : Delta[R/k_group][head_dim] then zero[R/k_group][head_dim] (meta_dtype), the
+ *             channel axis in operand order: position 32*q4+8*kk+e = channel 32*q4+slot(kk,e)
+ *   k_norms : n[R] (meta_dtype), token t at position (t%16)*8 + t/16
+ *   v_meta  : Delta[head_dim/v_group][R] then zero[head_dim/v_group][R] (meta_dtype),
+ *             token axis as in k_norms
  * Residual part, indexed [sequence][kv head]:
  *   res_k   : [R][head_dim] fp16, rotated and normalized keys K_u
  *   res_v   : [R][head_dim] io_dtype

@@ -193,27 +193,33 @@ extern "C" int oscar_debug_dump(const oscar_cache* c, int32_t b, int32_t h, int3
     OSCAR_HIP_CHECK(hipMemcpy(vm.data(), (const uint8_t*)c->v_meta + pg * g.v_meta_bytes, vm.size(), hipMemcpyDeviceToHost));
     for (int t = 0; t < R; ++t) {
       const size_t tok = (size_t)p * R + t;
+      const int tpos = tok_meta_pos(t);
       for (int j = 0; j < D; ++j) {
         if (k_codes) {
-          const int bit = j * bits;
-          k_codes[tok * D + j] = (uint8_t)((kc[(size_t)t * g.k_row_bytes + bit / 8] >> (bit % 8)) & mask);
+          // key chunk (tile t/16, n = t%16, q4 = j/32), code number j%32
+          const int bit = (j % 32) * bits;
+          const size_t off = (size_t)chunk_offset(bits, t / 16, t % 16, j / 32) + bit / 8;
+          k_codes[tok * D + j] = (uint8_t)((kc[off] >> (bit % 8)) & mask);
         }
         if (v_codes) {
-          const int bit = t * bits;
-          v_codes[tok * D + j] = (uint8_t)((vc[(size_t)j * g.v_row_bytes + bit / 8] >> (bit % 8)) & mask);
+          // value chunk (tile j/16, n = j%16, q4 = t%4), code number vtok_slot(t)
+          const int bit = vtok_slot(bits, t) * bits;
+          const size_t off = (size_t)chunk_offset(bits, j / 16, j % 16, vtok_q4(t)) + bit / 8;
+          v_codes[tok * D + j] = (uint8_t)((vc[off] >> (bit % 8)) & mask);
         }
       }
-      if (k_norm) k_norm[tok] = meta_at(kn, (size_t)t, c->cfg.meta_dtype);
+      if (k_norm) k_norm[tok] = meta_at(kn, (size_t)tpos, c->cfg.meta_dtype);
       for (int gv = 0; gv < g.ngv; ++gv) {
-        if (v_delta) v_delta[tok * g.ngv + gv] = meta_at(vm, (size_t)gv * R + t, c->cfg.meta_dtype);
-        if (v_zero) v_zero[tok * g.ngv + gv] = meta_at(vm, (size_t)(g.ngv + gv) * R + t, c->cfg.meta_dtype);
+        if (v_delta) v_delta[tok * g.ngv + gv] = meta_at(vm, (size_t)gv * R + tpos, c->cfg.meta_dtype);
+        if (v_zero) v_zero[tok * g.ngv + gv] = meta_at(vm, (size_t)(g.ngv + gv) * R + tpos, c->cfg.meta_dtype);
       }
     }
     for (int gk = 0; gk < g.ngk; ++gk)
       for (int j = 0; j < D; ++j) {
         const size_t row = (size_t)p * g.ngk + gk;
-        if (k_delta) k_delta[row * D + j] = meta_at(km, (size_t)gk * D + j, c->cfg.meta_dtype);
-        if (k_zero) k_zero[row * D + j] = meta_at(km, (size_t)(g.ngk + gk) * D + j, c->cfg.meta_dtype);
+        const int pos = kmeta_pos_of_chan(bits, j);
+        if (k_delta) k_delta[row * D + j] = meta_at(km, (size_t)gk * D + pos, c->cfg.meta_dtype);
+        if (k_zero) k_zero[row * D + j] = meta_at(km, (size_t)(g.ngk + gk) * D + pos, c->cfg.meta_dtype);
       }
   }
   const size_t sh = ((size_t)b * Hkv + h) * R;

@@ -43,6 +43,68 @@ __host__ __device__ inline PageGeom make_geom(int bits, int k_group, int v_group
   return g;
 }
 
+// ---- in-page layouts --------------------------------------------------------
+// The packed pools are laid out for the matrix-core decode kernel: a 64-lane wave
+// loads one 16x(32 codes) operand tile with one contiguous, fully used access, and a
+// lane's bytes are already in the order its MFMA operand registers want.
+//
+// A "chunk" is the 32 codes one lane owns of a 16 x 128 operand tile: lane (n, q4),
+// n = row/column of the tile (0..15), q4 = quarter of the contraction axis (0..3).
+// Inside a chunk, code number u (0..31) sits at bit u*bits (little endian) and feeds
+// MFMA k-step kk (0..3), vector element e (0..7) with u = slot_index(kk, e): the order
+// that falls out of unpacking 16-bit halves of a dword with masks only.
+//   keys   : tile = 16 tokens (n = t % 16, T = t / 16); chunk q4 = channels 32*q4 .. 32*q4+31,
+//            code u = channel 32*q4 + u.
+//   values : tile = 16 channels (n = c % 16, ct = c / 16); chunk q4 = tokens with t % 4 == q4,
+//            code slot_index(kk, e) = token 16*e + 4*kk + q4.
+// Tiles are stored in pairs so that a lane's two chunks are 16 (2-bit) or 32 (4-bit)
+// contiguous bytes: byte offset of chunk (tile, n, q4) =
+//   ((tile/2)*64 + n*4 + q4) * 2*CB + (tile%2)*CB,  CB = 4*bits bytes per chunk.
+__host__ __device__ constexpr int slot_index(int bits, int kk, int e) {
+  return bits == 2 ? 16 * (kk / 2) + 4 * (kk % 2) + e / 2 + 8 * (e % 2)
+                   : 8 * kk + e / 2 + 4 * (e % 2);
+}
+// Power-of-four weight of a slot after mask-only unpacking: the code lands in an fp16
+// subnormal/mantissa field as c * 4^(bits/2 * pexp) * 2^-24.
+__host__ __device__ constexpr int slot_pexp(int bits, int kk, int e) {
+  if (bits == 2) {
+    const int kap = 4 * (kk % 2) + e / 2;
+    return kap <= 4 ? kap : kap - 3;
+  }
+  return (e / 2) % 2;
+}
+__host__ __device__ constexpr int chunk_bytes(int bits) { return 4 * bits; }
+__host__ __device__ constexpr int chunk_offset(int bits, int tile, int n, int q4) {
+  return ((tile / 2) * 64 + n * 4 + q4) * 2 * chunk_bytes(bits) + (tile % 2) * chunk_bytes(bits);
+}
+// value side: token t -> (q4, code number inside the chunk)
+__host__ __device__ constexpr int vtok_q4(int t) { return t % 4; }
+__host__ __device__ constexpr int vtok_slot(int bits, int t) {
+  return slot_index(bits, (t / 4) % 4, t / 16);
+}
+// Per-token metadata (token norms, value Delta / zero) is stored in the order the
+// logits come out of the QK^T tiles: position (t % 16) * 8 + t / 16.
+__host__ __device__ constexpr int tok_meta_pos(int t) { return (t % 16) * 8 + t / 16; }
+// Key Delta / zero are stored in operand order: position 32*q4 + 8*kk + e holds channel
+// 32*q4 + slot_index(kk, e).
+__host__ __device__ constexpr int kmeta_chan_of_pos(int bits, int pos) {
+  return 32 * (pos / 32) + slot_index(bits, (pos % 32) / 8, pos % 8);
+}
+__host__ __device__ constexpr int kmeta_pos_of_chan(int bits, int j) {
+  const int q4 = j / 32, u = j % 32;
+  int kk = 0, e = 0;
+  if (bits == 2) {
+    const int d = u / 16, b = (u % 16) / 8, kap = u % 8;
+    kk = 2 * d + kap / 4;
+    e = 2 * (kap % 4) + b;
+  } else {
+    const int nu = u % 8;
+    kk = u / 8;
+    e = 2 * (nu % 4) + nu / 4;
+  }
+  return 32 * q4 + 8 * kk + e;
+}
+
 // ---- element conversions ----------------------------------------------------
 template <typename T> __device__ __forceinline__ float to_f32(T x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }

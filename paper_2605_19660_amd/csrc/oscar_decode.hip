@@ -42,6 +42,11 @@ __device__ __forceinline__ float load_meta(const void* p, size_t idx, int meta_b
   return __half2float(__ushort_as_half(reinterpret_cast<const uint16_t*>(p)[idx]));
 }
 
+// position of token t in "chunk order": quarter t%4 major, then its code number
+__device__ __forceinline__ int chunk_order(int bits, int t) {
+  return vtok_q4(t) * 32 + vtok_slot(bits, t);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
@@ -132,27 +137,36 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
     const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
 
     // issue the code loads early
+    // Two chunks of 32 codes each: channels 64*half .. +63 of this token, and tokens of
+    // quarters 2*th, 2*th+1 of this channel (chunk order).
     uint32_t kw[KWORDS], vw[KWORDS];
     {
-      const uint4* kp = reinterpret_cast<const uint4*>(kcodes + (size_t)tok * P.g.k_row_bytes + half * (P.g.k_row_bytes / 2));
-      const uint4* vp = reinterpret_cast<const uint4*>(vcodes + (size_t)ch * P.g.v_row_bytes + th * (P.g.v_row_bytes / 2));
+      constexpr int WPC = KWORDS / 2;  // words per chunk
 #pragma unroll
-      for (int i = 0; i < KWORDS / 4; ++i) {
-        uint4 a = kp[i], c = vp[i];
-        kw[4 * i] = a.x; kw[4 * i + 1] = a.y; kw[4 * i + 2] = a.z; kw[4 * i + 3] = a.w;
-        vw[4 * i] = c.x; vw[4 * i + 1] = c.y; vw[4 * i + 2] = c.z; vw[4 * i + 3] = c.w;
+      for (int i = 0; i < 2; ++i) {
+        const uint32_t* kp = reinterpret_cast<const uint32_t*>(
+            kcodes + chunk_offset(BITS, tok / 16, tok % 16, 2 * half + i));
+        const uint32_t* vp = reinterpret_cast<const uint32_t*>(
+            vcodes + chunk_offset(BITS, ch / 16, ch % 16, 2 * th + i));
+#pragma unroll
+        for (int w = 0; w < WPC; ++w) {
+          kw[i * WPC + w] = kp[w];
+          vw[i * WPC + w] = vp[w];
+        }
       }
     }
-    // (0) metadata -> LDS as fp32
+    // (0) metadata -> LDS as fp32, un-permuted (keys by channel, tokens in chunk order)
     for (int i = tid; i < ngk * D; i += 256) {
-      s_kd[i / D][i % D] = load_meta(kmeta, i, mb);
-      s_kz[i / D][i % D] = load_meta(kmeta, (size_t)ngk * D + i, mb);
+      const int gk = i / D, pos = kmeta_pos_of_chan(BITS, i % D);
+      s_kd[gk][i % D] = load_meta(kmeta, (size_t)gk * D + pos, mb);
+      s_kz[gk][i % D] = load_meta(kmeta, (size_t)(ngk + gk) * D + pos, mb);
     }
-    if (tid < R) s_norm[tid] = load_meta(knorm, tid, mb);
+    if (tid < R) s_norm[tid] = load_meta(knorm, tok_meta_pos(tid), mb);
     for (int i = tid; i < ngv * R; i += 256) {
-      const float dv = load_meta(vmeta, i, mb);
-      const float zv = load_meta(vmeta, (size_t)ngv * R + i, mb);
-      s_vdz[i / R][i % R] = make_float2(dv, -dv * zv);
+      const int gv = i / R, t = i % R;
+      const float dv = load_meta(vmeta, (size_t)gv * R + tok_meta_pos(t), mb);
+      const float zv = load_meta(vmeta, (size_t)(ngv + gv) * R + tok_meta_pos(t), mb);
+      s_vdz[gv][chunk_order(BITS, t)] = make_float2(dv, -dv * zv);
     }
     __syncthreads();
     // (1) A = Q_h * Delta_k, bias = sum_j A * z_k ; pair (group, head) -> one wave
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
 #pragma unroll
       for (int h = 0; h < GQ; ++h) {
         const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
-        if (half == 0) s_S[h][tok] = nrm * (tot - s_bias[gk][h]);
+        if (half == 0) s_S[h][chunk_order(BITS, tok)] = nrm * (tot - s_bias[gk][h]);
       }
     }
     __syncthreads();
@@ -287,7 +301,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
 #pragma unroll
       for (int h = 0; h < GQ; ++h) {
         const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
-        if (half == 0) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
+        if (half == 0) s_S[h][chunk_order(BITS, tok)] = tok < r ? nrm * tot : -INFINITY;
       }
     }
     __syncthreads();
@@ -314,7 +328,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
       for (int t = th * 64; t < t_end; ++t) {
         const float wv = load_io(P.c.res_v, (rb + t) * D + ch, P.c.cfg.io_dtype);
 #pragma unroll
-        for (int h = 0; h < GQ; ++h) o[h] = fmaf(s_S[h][t], wv, o[h]);
+        for (int h = 0; h < GQ; ++h) o[h] = fmaf(s_S[h][chunk_order(BITS, t)], wv, o[h]);
       }
     }
     __syncthreads();

@@ -26,6 +26,13 @@ constexpr int D = OSCAR_D;
 constexpr int R = OSCAR_R;
 constexpr int VROW_PAD = R + 4;  // LDS row stride (bytes) of the value code bytes
 
+// Staging position of value code (channel c, token t): rows are channels, columns are
+// tokens in chunk order (q4 = t%4 major, then k-step, then element), skewed per 32 rows to
+// spread LDS banks.
+__device__ __forceinline__ int vimg_index(int c, int t) {
+  return c * VROW_PAD + (c / 32) * 4 + (t % 4) * 32 + ((t / 4) % 4) * 8 + t / 16;
+}
+
 struct AppendParams {
   const void* k;
   const void* v;
@@ -199,11 +206,10 @@ template <typename IO, typename META, int BITS, int KG>
 __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   constexpr int NGK = R / KG;        // key groups per page
   constexpr int PPG = KG / 16;       // passes per key group
-  constexpr int KW = (BITS == 2) ? 1 : 2;  // 16-bit words per (token, 8 channels)
 
   __shared__ float s_red[NGK][4][D][2];
-  __shared__ __align__(16) uint16_t s_kimg[R][16 * KW];
-  __shared__ __align__(16) uint8_t s_vimg[D][VROW_PAD];
+  __shared__ __align__(16) uint8_t s_kimg[R * D * BITS / 8];     // key-code page image
+  __shared__ __align__(16) uint8_t s_vimg[D * VROW_PAD + 64];    // value codes, one per byte
   __shared__ __align__(16) META s_vmeta[2][4][R];
   __shared__ __align__(16) META s_norm[R];
 
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   }
   if (sub == 0) {
 #pragma unroll
-    for (int p = 0; p < 8; ++p) s_norm[p * 16 + slot] = from_f32<META>(nrm[p]);
+    for (int p = 0; p < 8; ++p) s_norm[tok_meta_pos(p * 16 + slot)] = from_f32<META>(nrm[p]);
   }
   __syncthreads();
 
@@ -342,8 +348,13 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       quant_params<META, BITS>(mn, mx, dfa[e], rda[e], za[e]);
     }
     if (slot == 0) {
-      store_meta8<META>(o_kmeta + (size_t)gk * D + sub * 8, dfa);
-      store_meta8<META>(o_kmeta + (size_t)(NGK + gk) * D + sub * 8, za);
+      // Delta / zero in operand order (see kmeta_pos_of_chan)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int pos = kmeta_pos_of_chan(BITS, sub * 8 + e);
+        o_kmeta[(size_t)gk * D + pos] = from_f32<META>(dfa[e]);
+        o_kmeta[(size_t)(NGK + gk) * D + pos] = from_f32<META>(za[e]);
+      }
     }
 #pragma unroll
     for (int p = gk * PPG; p < (gk + 1) * PPG; ++p) {
@@ -351,10 +362,13 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) w |= quant_code<BITS>(u[p][e], rda[e], za[e]) << (e * BITS);
       const int tok = p * 16 + slot;
+      // chunk (tile = tok/16, n = tok%16, q4 = sub/4); this thread's 8 codes are numbers
+      // 8*(sub%4) .. +7 of the chunk
+      const int off = chunk_offset(BITS, tok / 16, tok % 16, sub / 4) + (sub % 4) * BITS;
       if (BITS == 2) {
-        s_kimg[tok][sub] = (uint16_t)w;
+        *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)w;
       } else {
-        *reinterpret_cast<uint32_t*>(&s_kimg[tok][sub * 2]) = w;
+        *reinterpret_cast<uint32_t*>(&s_kimg[off]) = w;
       }
     }
   }
@@ -378,57 +392,59 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     const int tok = p * 16 + slot;
     if ((sub & (lanes_per_vgroup - 1)) == 0) {
       const int gv = sub / lanes_per_vgroup;
-      s_vmeta[0][gv][tok] = from_f32<META>(df);
-      s_vmeta[1][gv][tok] = from_f32<META>(z);
+      s_vmeta[0][gv][tok_meta_pos(tok)] = from_f32<META>(df);
+      s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(z);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      s_vimg[sub * 8 + e][tok] = (uint8_t)quant_code<BITS>(vv[p][e], rd, z);
+      s_vimg[vimg_index(sub * 8 + e, tok)] = (uint8_t)quant_code<BITS>(vv[p][e], rd, z);
   }
   __syncthreads();
 
   // ---- phase 4: coalesced page stores ----
   {
-    const uint4* src = reinterpret_cast<const uint4*>(&s_kimg[0][0]);
+    const uint4* src = reinterpret_cast<const uint4*>(&s_kimg[0]);
     uint4* dst = reinterpret_cast<uint4*>(o_kcodes);
-    constexpr int NV = R * 16 * KW * 2 / 16;  // uint4 count: 256 (2-bit) or 512 (4-bit)
+    constexpr int NV = R * D * BITS / 8 / 16;  // uint4 count: 256 (2-bit) or 512 (4-bit)
 #pragma unroll
     for (int i = tid; i < NV; i += 256) dst[i] = src[i];
   }
   {
-    const int c = tid >> 1, half = tid & 1;
-    const uint32_t* row = reinterpret_cast<const uint32_t*>(&s_vimg[c][half * 64]);
+    // thread = (tile pair tp, n, q4): packs the chunks of channels 32*tp+n and 32*tp+16+n
+    const int tp = tid >> 6, n = (tid >> 2) & 15, q4 = tid & 3;
+    uint32_t outw[2][BITS];  // [channel of the pair][dword of the chunk]
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const int c = 32 * tp + 16 * cc + n;
+      const uint32_t* row = reinterpret_cast<const uint32_t*>(&s_vimg[vimg_index(c, q4)]);
+#pragma unroll
+      for (int d = 0; d < BITS; ++d) outw[cc][d] = 0;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        // bytes of elements e = 0..3 and e = 4..7 of k-step kk
+        const uint32_t x0 = row[2 * kk], x1 = row[2 * kk + 1];
+        if (BITS == 2) {
+          const uint32_t ev = (x0 & 3u) | (((x0 >> 16) & 3u) << 2) | ((x1 & 3u) << 4) |
+                              (((x1 >> 16) & 3u) << 6);
+          const uint32_t od = ((x0 >> 8) & 3u) | (((x0 >> 24) & 3u) << 2) |
+                              (((x1 >> 8) & 3u) << 4) | (((x1 >> 24) & 3u) << 6);
+          // even elements -> code numbers 4*(kk%2)+r, odd elements -> 8 more
+          outw[cc][kk / 2] |= (ev << (8 * (kk % 2))) | (od << (16 + 8 * (kk % 2)));
+        } else {
+          const uint32_t ev = (x0 & 15u) | (((x0 >> 16) & 15u) << 4) | ((x1 & 15u) << 8) |
+                              (((x1 >> 16) & 15u) << 12);
+          const uint32_t od = ((x0 >> 8) & 15u) | (((x0 >> 24) & 15u) << 4) |
+                              (((x1 >> 8) & 15u) << 8) | (((x1 >> 24) & 15u) << 12);
+          outw[cc][kk] = ev | (od << 16);
+        }
+      }
+    }
+    uint8_t* dst = o_vcodes + (size_t)tid * 2 * chunk_bytes(BITS);
     if (BITS == 2) {
-      uint32_t outw[4];
-#pragma unroll
-      for (int wv = 0; wv < 4; ++wv) {
-        uint32_t acc = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          uint32_t x = row[wv * 4 + q];
-          uint32_t pk = (x & 0x3u) | ((x >> 6) & 0xCu) | ((x >> 12) & 0x30u) | ((x >> 18) & 0xC0u);
-          acc |= pk << (8 * q);
-        }
-        outw[wv] = acc;
-      }
-      *reinterpret_cast<uint4*>(o_vcodes + c * 32 + half * 16) =
-          make_uint4(outw[0], outw[1], outw[2], outw[3]);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(outw[0][0], outw[0][1], outw[1][0], outw[1][1]);
     } else {
-      uint32_t outw[8];
-#pragma unroll
-      for (int wv = 0; wv < 8; ++wv) {
-        uint32_t acc = 0;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          uint32_t x = row[wv * 2 + q];
-          uint32_t pk = (x & 0xFu) | ((x >> 4) & 0xF0u) | ((x >> 8) & 0xF00u) | ((x >> 12) & 0xF000u);
-          acc |= pk << (16 * q);
-        }
-        outw[wv] = acc;
-      }
-      uint4* dst = reinterpret_cast<uint4*>(o_vcodes + c * 64 + half * 32);
-      dst[0] = make_uint4(outw[0], outw[1], outw[2], outw[3]);
-      dst[1] = make_uint4(outw[4], outw[5], outw[6], outw[7]);
+      reinterpret_cast<uint4*>(dst)[0] = make_uint4(outw[0][0], outw[0][1], outw[0][2], outw[0][3]);
+      reinterpret_cast<uint4*>(dst)[1] = make_uint4(outw[1][0], outw[1][1], outw[1][2], outw[1][3]);
     }
   }
   {

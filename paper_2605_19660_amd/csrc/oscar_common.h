@@ -64,15 +64,19 @@ __host__ __device__ constexpr int slot_index(int bits, int kk, int e) {
   return bits == 2 ? 16 * (kk / 2) + 4 * (kk % 2) + e / 2 + 8 * (e % 2)
                    : 8 * kk + e / 2 + 4 * (e % 2);
 }
-// Power-of-four weight of a slot after mask-only unpacking: the code lands in an fp16
-// subnormal/mantissa field as c * 4^(bits/2 * pexp) * 2^-24.
-__host__ __device__ constexpr int slot_pexp(int bits, int kk, int e) {
+// Weight of a slot after shift-and-mask unpacking: the code lands at bit offset
+// slot_bitpos of an fp16 lane's mantissa, i.e. as the number c * 2^slot_bitpos * 2^-24.
+// Only offsets 4,6,8 are used for 2-bit codes and 2,6 for 4-bit codes: the MFMA aligns
+// products by the operands' nominal exponents, so codes parked far below the top of the
+// mantissa (or a wide spread of offsets) cost accumulation precision.
+__host__ __device__ constexpr int slot_bitpos(int bits, int kk, int e) {
   if (bits == 2) {
-    const int kap = 4 * (kk % 2) + e / 2;
-    return kap <= 4 ? kap : kap - 3;
+    const int kap = 4 * (kk % 2) + e / 2;  // bit pair inside the 16-bit half
+    return 2 * (kap == 0 ? 2 : kap == 1 ? 3 : kap <= 4 ? kap : kap - 3);
   }
-  return (e / 2) % 2;
+  return ((e / 2) % 2) ? 6 : 2;
 }
+__host__ __device__ constexpr int slot_bitpos_min(int bits) { return bits == 2 ? 4 : 2; }
 __host__ __device__ constexpr int chunk_bytes(int bits) { return 4 * bits; }
 __host__ __device__ constexpr int chunk_offset(int bits, int tile, int n, int q4) {
   return ((tile / 2) * 64 + n * 4 + q4) * 2 * chunk_bytes(bits) + (tile % 2) * chunk_bytes(bits);
@@ -133,6 +137,10 @@ int oscar_validate_config(const oscar_config* cfg);
 // Reduce pass of split-K decode (defined with the decode kernels).
 void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int out_dtype,
                                 int n_q_heads, int batch, hipStream_t st);
+
+// Matrix-core partial pass (params = the decode parameter block); returns
+// OSCAR_ERR_UNSUPPORTED when the configuration must take the generic kernel.
+int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st);
 
 #define OSCAR_HIP_CHECK(expr)                 \
   do {                                        \

@@ -11,73 +11,9 @@
 // are built once per page, so logit = n_i * (sum_j A * c - bias); on the value side
 // w = Delta_v * c + (-Delta_v * z_v) is one fused multiply-add per element.
 // One workgroup serves all query heads of a kv head, so every packed byte is read once.
-#include "oscar_common.h"
+#include "oscar_decode_common.h"
 
 namespace {
-
-constexpr int D = OSCAR_D;
-constexpr int R = OSCAR_R;
-constexpr int WS_STRIDE = D + 2;  // partial record: o[128], m, l
-
-struct DecodeParams {
-  const void* q;
-  void* out;
-  float* ws;
-  oscar_cache c;
-  PageGeom g;
-  int num_splits;
-  float qk_scale_log2;  // softmax scale * log2(e)
-  int out_dtype;
-};
-
-__device__ __forceinline__ float load_io(const void* p, size_t idx, int dt) {
-  if (dt == OSCAR_F32) return reinterpret_cast<const float*>(p)[idx];
-  const uint16_t h = reinterpret_cast<const uint16_t*>(p)[idx];
-  if (dt == OSCAR_BF16) return __uint_as_float((uint32_t)h << 16);
-  return __half2float(__ushort_as_half(h));
-}
-
-__device__ __forceinline__ float load_meta(const void* p, size_t idx, int meta_bytes) {
-  if (meta_bytes == 4) return reinterpret_cast<const float*>(p)[idx];
-  return __half2float(__ushort_as_half(reinterpret_cast<const uint16_t*>(p)[idx]));
-}
-
-// position of token t in "chunk order": quarter t%4 major, then its code number
-__device__ __forceinline__ int chunk_order(int bits, int t) {
-  return vtok_q4(t) * 32 + vtok_slot(bits, t);
-}
-
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
-}
-
-// Q_h = H(q)/sqrt(128) for GQ heads in LDS, times scale*log2(e).
-template <int GQ>
-__device__ __forceinline__ void rotate_queries(float (*s_q)[D], const void* q, size_t q_base,
-                                               int io_dtype, float mul, int tid) {
-  for (int i = tid; i < GQ * D; i += 256) s_q[i / D][i % D] = load_io(q, q_base + i, io_dtype);
-  __syncthreads();
-  for (int h = 1; h < D; h <<= 1) {
-    for (int i = tid; i < GQ * (D / 2); i += 256) {
-      const int head = i / (D / 2), pr = i % (D / 2);
-      const int lo = ((pr & ~(h - 1)) << 1) | (pr & (h - 1));  // index with bit h clear
-      const float a = s_q[head][lo], b = s_q[head][lo | h];
-      s_q[head][lo] = a + b;
-      s_q[head][lo | h] = a - b;
-    }
-    __syncthreads();
-  }
-  const float c = 0.08838834764831845f * mul;
-  for (int i = tid; i < GQ * D; i += 256) s_q[i / D][i % D] *= c;
-  __syncthreads();
-}
 
 template <int BITS, int GQ>
 __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams P) {
@@ -118,8 +54,8 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
 
   const bool any_work = (pg0 < pg1) || has_res;
   if (any_work) {
-    rotate_queries<GQ>(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * GQ) * D, P.c.cfg.io_dtype,
-                       P.qk_scale_log2, tid);
+    rotate_queries(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * GQ) * D, P.c.cfg.io_dtype,
+                   P.qk_scale_log2, tid, GQ);
   } else {
     __syncthreads();
   }
@@ -432,7 +368,9 @@ extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache
   const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
   dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st) : launch_gq<4>(P, gq, grid, st);
+  rc = oscar_launch_decode_mfma(&P, gq, grid, st);
+  if (rc == OSCAR_ERR_UNSUPPORTED)
+    rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st) : launch_gq<4>(P, gq, grid, st);
   if (rc != OSCAR_OK) return rc;
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
   return OSCAR_OK;

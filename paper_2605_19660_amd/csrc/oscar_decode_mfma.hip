@@ -1,0 +1,600 @@
+// oscar_decode_attn, matrix-core path for gfx950 (v_mfma_f32_16x16x32_f16).
+//
+// Why matrix cores: at 86 bytes per token and kv head, 70 % of 8 TB/s leaves about 600
+// plain-ALU lane operations per token and kv head on 256 CUs; the two GQA-batched
+// contractions alone (q K^T and P V, 4..8 query heads per kv head) need 1024..2048 fused
+// multiply-adds.  Everything that is a contraction therefore runs on MFMA; unpacking,
+// softmax and scale folding stay on the vector ALU.
+//
+//   logit[h][t] = n_t * ( sum_j (Q_h[h][j] Delta_k[j]) c_k[t][j]  -  sum_j Q_h[h][j] Delta_k[j] z_k[j] )
+//   out[h][c]   = sum_t (p[h][t] Delta_v[t][G(c)]) c_v[t][c]  -  sum_t p[h][t] Delta_v[t][G(c)] z_v[t][G(c)]
+// (logits of App. "Implementation Details", "Overall Design"; dequantization of Eq. 3-4.)
+//
+// Exactness devices:
+//  * Codes become fp16 operands with one AND per register and no offset: a code parked at
+//    bit offset s of an fp16 lane's mantissa (exponent field zero) is the subnormal number
+//    c * 2^s * 2^-24, and the MFMA keeps fp16 subnormals.  2^s is divided out of the other
+//    operand.  Offsets stay near the top of the mantissa (see slot_bitpos).
+//  * The other operand (Q_h*Delta_k, resp. p*Delta_v) is fp32 split into fp16 hi + lo,
+//    carried as two rows of the 16-row MFMA tile (rows are otherwise idle for GQA <= 8),
+//    so products are exact and accumulation is fp32.
+//  * Zero-points are subtracted analytically in fp32 (the two right-hand sums above).
+//
+// Work decomposition: grid (split, kv head, sequence); 4 waves per workgroup, every wave
+// owns whole pages (no barriers in the page loop) and keeps its own online-softmax state;
+// the 4 wave states and the 16-bit residual tokens (handled by the workgroup of the last
+// split with plain ALU code) are merged through LDS at the end.
+// Tile roles: q K^T uses M = query-head limb rows, N = 16 tokens, K = 128 channels;
+// P V uses M = query-head limb rows, N = 16 channels, K = 128 tokens.  A lane of the logit
+// tile is (token n, head group q4), which is also the lane that owns the 8-token operand
+// vector (k-step n/4, quarter n%4) of the P V contraction: probabilities go to LDS as
+// 16-byte vectors and come back as MFMA A-operands without any shuffle.
+#include <stdlib.h>
+
+#include "oscar_decode_common.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// wave-local LDS hand-off: LDS operations of one wave execute in order; this only stops
+// the compiler from moving accesses across the hand-off point.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float row16_max(float v) {
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+__device__ __forceinline__ void halves_to_f32(const uint4& r, float (&x)[8]) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
+    x[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+  }
+}
+
+__device__ __forceinline__ uint32_t pack_rtz(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+// fp32 x[8] -> fp16 hi[8] (4 dwords) + fp16 lo[8] with hi + lo = x to ~2^-22
+__device__ __forceinline__ void split_hi_lo(const float (&x)[8], uint4& hi, uint4& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_rtz(x[2 * i], x[2 * i + 1]);
+    const half2v hv = __builtin_bit_cast(half2v, h[i]);
+    l[i] = pack_rtz(x[2 * i] - (float)hv[0], x[2 * i + 1] - (float)hv[1]);
+  }
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+// One 32-code chunk -> the four B-operand vectors (k-steps 0..3) of a 16x16x32 MFMA.
+template <int BITS> struct Chunk;
+template <> struct Chunk<2> {
+  uint32_t w[2];
+  __device__ __forceinline__ void operands(u32x4 (&b)[4]) const {
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+      // bit pairs 0,1 via << 4 (-> positions 4, 6), pairs 2,3,4 in place, pairs 5,6,7 via >> 6
+      const uint32_t x = w[d], y = x >> 6, z = x << 4;
+      b[2 * d] = (u32x4){z & 0x00300030u, z & 0x00C000C0u, x & 0x00300030u, x & 0x00C000C0u};
+      b[2 * d + 1] = (u32x4){x & 0x03000300u, y & 0x00300030u, y & 0x00C000C0u, y & 0x03000300u};
+    }
+  }
+};
+template <> struct Chunk<4> {
+  uint32_t w[4];
+  __device__ __forceinline__ void operands(u32x4 (&b)[4]) const {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      // nibbles 0,1 via << 2 (-> bit offsets 2, 6), nibbles 2,3 via >> 6
+      const uint32_t x = w[d], y = x >> 6, z = x << 2;
+      b[d] = (u32x4){z & 0x003C003Cu, z & 0x03C003C0u, y & 0x003C003Cu, y & 0x03C003C0u};
+    }
+  }
+};
+
+// A lane's two chunks of a tile pair: 16 bytes (2-bit) or 32 bytes (4-bit).
+template <int BITS> struct TilePair;
+template <> struct TilePair<2> {
+  uint4 v;
+  __device__ __forceinline__ void load(const uint8_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ Chunk<2> chunk(int i) const {
+    Chunk<2> c;
+    c.w[0] = i ? v.z : v.x;
+    c.w[1] = i ? v.w : v.y;
+    return c;
+  }
+};
+template <> struct TilePair<4> {
+  uint4 v[2];
+  __device__ __forceinline__ void load(const uint8_t* p) {
+    v[0] = reinterpret_cast<const uint4*>(p)[0];
+    v[1] = reinterpret_cast<const uint4*>(p)[1];
+  }
+  __device__ __forceinline__ Chunk<4> chunk(int i) const {
+    Chunk<4> c;
+    c.w[0] = v[i].x; c.w[1] = v[i].y; c.w[2] = v[i].z; c.w[3] = v[i].w;
+    return c;
+  }
+};
+
+// Everything one wave needs of one page, in registers (prefetched one page ahead).
+template <int BITS, int NGK, int NGV> struct PageRegs {
+  TilePair<BITS> kc[4], vc[4];
+  uint4 kd[NGK], kz[NGK];  // key Delta / zero of positions 8n..8n+7 (operand order)
+  uint4 nr;                // norms of tokens 16*T+n, T = 0..7
+  uint4 vd[NGV], vz[NGV];  // value Delta / zero of the same tokens
+
+  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane) {
+    const int n = lane & 15, q4 = lane >> 4;
+    const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(P.c.k_codes) + pgi * P.g.k_codes_bytes;
+    const uint8_t* vcodes = reinterpret_cast<const uint8_t*>(P.c.v_codes) + pgi * P.g.v_codes_bytes;
+    const uint8_t* kmeta = reinterpret_cast<const uint8_t*>(P.c.k_meta) + pgi * P.g.k_meta_bytes;
+    const uint8_t* knorm = reinterpret_cast<const uint8_t*>(P.c.k_norms) + pgi * P.g.k_norms_bytes;
+    const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
+    constexpr int PB = 2 * chunk_bytes(BITS);  // bytes of a lane's tile pair
+#pragma unroll
+    for (int tp = 0; tp < 4; ++tp) {
+      kc[tp].load(kcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
+      vc[tp].load(vcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
+    }
+#pragma unroll
+    for (int g = 0; g < NGK; ++g) {
+      kd[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)(g * D + 8 * n) * 2);
+      kz[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)((NGK + g) * D + 8 * n) * 2);
+    }
+    nr = *reinterpret_cast<const uint4*>(knorm + (size_t)(8 * n) * 2);
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) {
+      vd[g] = *reinterpret_cast<const uint4*>(vmeta + (size_t)(g * R + 8 * n) * 2);
+      vz[g] = *reinterpret_cast<const uint4*>(vmeta + (size_t)((NGV + g) * R + 8 * n) * 2);
+    }
+  }
+};
+
+// rows of the 16-row operand tile: head h -> hi row 4*(h%4) + 2*(h/4), lo row + 1, so the
+// accumulator lane group q4 (rows 4*q4..4*q4+3) owns heads q4 (slot 0) and q4+4 (slot 1).
+__device__ __forceinline__ int row_hi(int h) { return 4 * (h & 3) + 2 * (h >> 2); }
+
+template <int BITS, int HP, int NGK, int NGV>
+__global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
+  constexpr int TPG = 8 / NGK;  // token tiles per key group
+  constexpr int CPG = 8 / NGV;  // channel tiles per value group
+
+  __shared__ __align__(16) float s_q[OSCAR_MAX_GQA][D];
+  __shared__ __align__(16) _Float16 s_A[4][16][D];   // per wave: (Q_h Delta_k) hi/lo rows
+  __shared__ __align__(16) _Float16 s_P[4][16][D];   // per wave: (p Delta_v) hi/lo rows
+  __shared__ __align__(16) float s_o[4][OSCAR_MAX_GQA][D];  // wave results for the merge
+  __shared__ float s_wm[5][OSCAR_MAX_GQA], s_wl[5][OSCAR_MAX_GQA];
+  // residual phase
+  __shared__ float s_norm[R];
+  __shared__ __align__(16) float s_S[OSCAR_MAX_GQA][R];
+  __shared__ float s_alpha[OSCAR_MAX_GQA];
+
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, q4 = lane >> 4;
+  const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
+
+  const int seq_len = P.c.seq_lens[b];
+  const int r = P.c.res_lens[b];
+  const int n_pages = (seq_len - r) / R;
+  const int pps = (n_pages + P.num_splits - 1) / P.num_splits;
+  const int pg0 = split * pps;
+  const int pg1 = min(n_pages, pg0 + pps);
+  const bool has_res = (split == P.num_splits - 1) && r > 0;
+  const bool any_work = (pg0 < pg1) || has_res;
+
+  // zero the operand tables (rows of absent heads stay zero) and rotate the queries
+  for (int i = tid; i < 4 * 16 * D / 2; i += 256) {
+    reinterpret_cast<uint32_t*>(&s_A[0][0][0])[i] = 0u;
+    reinterpret_cast<uint32_t*>(&s_P[0][0][0])[i] = 0u;
+  }
+  if (any_work) {
+    rotate_queries(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * gq) * D, P.c.cfg.io_dtype,
+                   P.qk_scale_log2, tid, gq);
+  } else {
+    __syncthreads();
+  }
+
+  // ---- per-lane constants ----
+  // writer role for the key operand: positions 8n..8n+7 of heads q4 (+4)
+  float qr[HP][8], qs[HP][8], ps[HP];
+#pragma unroll
+  for (int s = 0; s < HP; ++s) {
+    const int h = q4 + 4 * s;
+    float mx = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int chan = 32 * (n >> 2) + slot_index(BITS, n & 3, i);
+      qr[s][i] = (h < gq && any_work) ? s_q[h][chan] : 0.0f;
+      mx = fmaxf(mx, fabsf(qr[s][i]));
+    }
+    mx = row16_max(mx);
+    int ex = 0;
+    (void)frexpf(mx, &ex);           // mx < 2^ex
+    if (mx == 0.0f) ex = 0;
+    // |Q_h| * 2^(xh - bitpos) < 2^14 for every slot, and Delta_k <= 1
+    const int xh = 14 + slot_bitpos_min(BITS) - ex;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qs[s][i] = ldexpf(qr[s][i], xh - slot_bitpos(BITS, n & 3, i));
+    ps[s] = ldexpf(1.0f, 24 - xh);
+  }
+  // value side: this lane's tokens 16*T+n feed k-step n/4, element T
+  float vsc0[8];
+#pragma unroll
+  for (int T = 0; T < 8; ++T)
+    vsc0[T] = ldexpf(1.0f, slot_bitpos_min(BITS) - slot_bitpos(BITS, n >> 2, T));
+
+  // ---- wave state ----
+  float m_run[HP], l_run[HP], bv[HP][NGV];
+  float4v O[8];
+#pragma unroll
+  for (int s = 0; s < HP; ++s) {
+    m_run[s] = -INFINITY;
+    l_run[s] = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) bv[s][g] = 0.0f;
+  }
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) O[ct] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
+  int xv_cur = 0;
+
+  _Float16(*A_tab)[D] = s_A[wave];
+  _Float16(*P_tab)[D] = s_P[wave];
+
+  PageRegs<BITS, NGK, NGV> cur;
+  int pg = pg0 + wave;
+  if (pg < pg1) {
+    const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + pg];
+    cur.load(P, (size_t)phys * Hkv + kvh, lane);
+  }
+  for (; pg < pg1; pg += 4) {
+    PageRegs<BITS, NGK, NGV> nxt;
+    const bool has_next = pg + 4 < pg1;
+    if (has_next) {
+      const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + pg + 4];
+      nxt.load(P, (size_t)phys * Hkv + kvh, lane);
+    }
+
+    // token norms of this lane's 8 tokens
+    float nt[8];
+    halves_to_f32(cur.nr, nt);
+
+    // ---- q K^T ----
+    float S[HP][8];
+#pragma unroll
+    for (int g = 0; g < NGK; ++g) {
+      float dk[8], zk[8];
+      halves_to_f32(cur.kd[g], dk);
+      halves_to_f32(cur.kz[g], zk);
+      float bias[HP];
+#pragma unroll
+      for (int s = 0; s < HP; ++s) {
+        float a[8], bp = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          a[i] = qs[s][i] * dk[i];
+          bp = fmaf(qr[s][i] * dk[i], zk[i], bp);
+        }
+        bias[s] = row16_sum(bp);
+        uint4 hi, lo;
+        split_hi_lo(a, hi, lo);
+        const int h = q4 + 4 * s;
+        if (h < gq) {
+          *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
+          *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
+        }
+      }
+      wave_lds_fence();
+      half8 areg[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        areg[kk] = *reinterpret_cast<const half8*>(&A_tab[n][32 * q4 + 8 * kk]);
+      wave_lds_fence();
+#pragma unroll
+      for (int tt = 0; tt < TPG; ++tt) {
+        const int T = g * TPG + tt;
+        u32x4 bop[4];
+        cur.kc[T >> 1].chunk(T & 1).operands(bop);
+        float4v acc = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(areg[kk], __builtin_bit_cast(half8, bop[kk]),
+                                                       acc, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < HP; ++s)
+          S[s][T] = nt[T] * fmaf(acc[2 * s] + acc[2 * s + 1], ps[s], -bias[s]);
+      }
+    }
+
+    // ---- online softmax (per head slot; the 16 lanes of a group share a head) ----
+    float p[HP][8], alpha[HP];
+    bool rescale = false;
+#pragma unroll
+    for (int s = 0; s < HP; ++s) {
+      float mx = S[s][0];
+#pragma unroll
+      for (int T = 1; T < 8; ++T) mx = fmaxf(mx, S[s][T]);
+      const float m_new = fmaxf(m_run[s], row16_max(mx));
+      alpha[s] = __builtin_amdgcn_exp2f(m_run[s] - m_new);
+      rescale |= (m_new != m_run[s]);
+      m_run[s] = m_new;
+      float sum = 0.0f;
+#pragma unroll
+      for (int T = 0; T < 8; ++T) {
+        p[s][T] = __builtin_amdgcn_exp2f(S[s][T] - m_new);
+        sum += p[s][T];
+      }
+      l_run[s] = l_run[s] * alpha[s] + sum;
+    }
+
+    // ---- page scale of the value operand: Delta_v * 2^xv < 2^13 ----
+    float dv[NGV][8];
+    float dmax = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) {
+      halves_to_f32(cur.vd[g], dv[g]);
+#pragma unroll
+      for (int T = 0; T < 8; ++T) dmax = fmaxf(dmax, dv[g][T]);
+    }
+    dmax = wave_max(dmax);
+    int exv = 0;
+    (void)frexpf(dmax, &exv);
+    if (!(dmax > 0.0f) || isinf(dmax)) exv = 0;
+    const int xv = 13 - exv;
+    rescale |= (xv != xv_cur);
+    if (__any(rescale)) {
+      float f[HP];
+#pragma unroll
+      for (int s = 0; s < HP; ++s) f[s] = ldexpf(alpha[s], xv - xv_cur);
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+#pragma unroll
+        for (int s = 0; s < HP; ++s) {
+          O[ct][2 * s] *= f[s];
+          O[ct][2 * s + 1] *= f[s];
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < HP; ++s)
+#pragma unroll
+        for (int g = 0; g < NGV; ++g) bv[s][g] *= alpha[s];
+    }
+    xv_cur = xv;
+
+    // ---- P V, one value group at a time through the wave's LDS table ----
+    float pt[HP][8];
+#pragma unroll
+    for (int s = 0; s < HP; ++s)
+#pragma unroll
+      for (int T = 0; T < 8; ++T) pt[s][T] = ldexpf(p[s][T] * vsc0[T], xv);
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) {
+      float zv[8];
+      halves_to_f32(cur.vz[g], zv);
+#pragma unroll
+      for (int s = 0; s < HP; ++s) {
+        float a[8], acc_b = 0.0f;
+#pragma unroll
+        for (int T = 0; T < 8; ++T) {
+          a[T] = pt[s][T] * dv[g][T];
+          acc_b = fmaf(p[s][T] * dv[g][T], zv[T], acc_b);
+        }
+        bv[s][g] += acc_b;
+        uint4 hi, lo;
+        split_hi_lo(a, hi, lo);
+        const int h = q4 + 4 * s;
+        if (h < gq) {
+          *reinterpret_cast<uint4*>(&P_tab[row_hi(h)][8 * n]) = hi;
+          *reinterpret_cast<uint4*>(&P_tab[row_hi(h) + 1][8 * n]) = lo;
+        }
+      }
+      wave_lds_fence();
+      half8 preg[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        preg[kk] = *reinterpret_cast<const half8*>(&P_tab[n][8 * (4 * kk + q4)]);
+      wave_lds_fence();
+#pragma unroll
+      for (int cc = 0; cc < CPG; ++cc) {
+        const int ct = g * CPG + cc;
+        u32x4 bop[4];
+        cur.vc[ct >> 1].chunk(ct & 1).operands(bop);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(preg[kk], __builtin_bit_cast(half8, bop[kk]),
+                                                         O[ct], 0, 0, 0);
+      }
+    }
+    if (has_next) cur = nxt;
+  }
+
+  // ---- wave results -> LDS ----
+  {
+    const float unscale = ldexpf(1.0f, 24 - xv_cur - slot_bitpos_min(BITS));
+#pragma unroll
+    for (int s = 0; s < HP; ++s) {
+      const int h = q4 + 4 * s;
+      const float l_tot = row16_sum(l_run[s]);
+      float bvt[NGV];
+#pragma unroll
+      for (int g = 0; g < NGV; ++g) bvt[g] = row16_sum(bv[s][g]);
+      if (h < gq) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct)
+          s_o[wave][h][16 * ct + n] = (O[ct][2 * s] + O[ct][2 * s + 1]) * unscale - bvt[ct / CPG];
+        if (n == 0) {
+          s_wm[wave][h] = m_run[s];
+          s_wl[wave][h] = l_tot;
+        }
+      }
+    }
+  }
+
+  // ---- residual tokens (last split): plain-ALU attention over fp16 K_u and raw V ----
+  const int tok = tid >> 1, half = tid & 1;  // logits: (token, channel half)
+  const int ch = tid >> 1, th = tid & 1;     // values: (channel, token half)
+  float o_res[OSCAR_MAX_GQA];
+#pragma unroll
+  for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] = 0.0f;
+  if (tid < OSCAR_MAX_GQA) {
+    s_wm[4][tid] = -INFINITY;
+    s_wl[4][tid] = 0.0f;
+  }
+  if (has_res) {
+    const int mb = P.g.meta_bytes;
+    const size_t rb = ((size_t)b * Hkv + kvh) * R;
+    const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
+    if (tid < R) s_norm[tid] = tid < r ? load_meta(P.c.res_norm, rb + tid, mb) : 0.0f;
+    __syncthreads();
+    {
+      float acc[OSCAR_MAX_GQA];
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) acc[h] = 0.0f;
+      if (tok < r) {
+        const uint4* kp = reinterpret_cast<const uint4*>(rk + (size_t)tok * D + half * 64);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float kv[8];
+          halves_to_f32(kp[i], kv);
+          const int j = half * 64 + i * 8;
+#pragma unroll
+          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+            if (h < gq) {
+              const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
+              const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
+              acc[h] = fmaf(qa.x, kv[0], acc[h]);
+              acc[h] = fmaf(qa.y, kv[1], acc[h]);
+              acc[h] = fmaf(qa.z, kv[2], acc[h]);
+              acc[h] = fmaf(qa.w, kv[3], acc[h]);
+              acc[h] = fmaf(qb.x, kv[4], acc[h]);
+              acc[h] = fmaf(qb.y, kv[5], acc[h]);
+              acc[h] = fmaf(qb.z, kv[6], acc[h]);
+              acc[h] = fmaf(qb.w, kv[7], acc[h]);
+            }
+          }
+        }
+      }
+      const float nrm = s_norm[tok];
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
+        if (half == 0 && h < gq) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
+      }
+    }
+    __syncthreads();
+    for (int h = wave; h < gq; h += 4) {
+      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
+      const float m_new = wave_max(fmaxf(s0, s1));
+      const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
+      const float sum = wave_sum(p0 + p1);
+      s_S[h][lane] = p0;
+      s_S[h][lane + 64] = p1;
+      if (lane == 0) {
+        s_wm[4][h] = m_new;
+        s_wl[4][h] = sum;
+      }
+    }
+    __syncthreads();
+    {
+      const int t_end = min(r, th * 64 + 64);
+      for (int t = th * 64; t < t_end; ++t) {
+        const float wv = load_io(P.c.res_v, (rb + t) * D + ch, P.c.cfg.io_dtype);
+#pragma unroll
+        for (int h = 0; h < OSCAR_MAX_GQA; ++h)
+          if (h < gq) o_res[h] = fmaf(s_S[h][t], wv, o_res[h]);
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- merge the 4 wave states and the residual state, write the split's record ----
+  // o_res holds this thread's token half of the residual sum; add the partner's
+#pragma unroll
+  for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] += __shfl_xor(o_res[h], 1, 64);
+#pragma unroll
+  for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+    if (h < gq && (h & 1) == th) {
+      float M = s_wm[4][h];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
+      float acc = 0.0f;
+      if (M != -INFINITY) {
+        acc = o_res[h] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          if (s_wm[w][h] != -INFINITY) acc += s_o[w][h][ch] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);
+      }
+      const size_t rec = ((size_t)b * Hq + (size_t)kvh * gq + h) * P.num_splits + split;
+      P.ws[rec * WS_STRIDE + ch] = acc;
+    }
+  }
+  if (tid < gq) {
+    const int h = tid;
+    float M = s_wm[4][h];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
+    float L = 0.0f;
+    if (M != -INFINITY) {
+      L = s_wl[4][h] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        if (s_wm[w][h] != -INFINITY) L += s_wl[w][h] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);
+    }
+    const size_t rec = ((size_t)b * Hq + (size_t)kvh * gq + h) * P.num_splits + split;
+    P.ws[rec * WS_STRIDE + D] = M;
+    P.ws[rec * WS_STRIDE + D + 1] = L;
+  }
+}
+
+template <int BITS, int HP>
+int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
+  const int ngk = P.g.ngk, ngv = P.g.ngv;
+#define OSCAR_MFMA_CASE(NK, NV)                                                          \
+  if (ngk == NK && ngv == NV) {                                                          \
+    hipLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV>), grid, dim3(256), 0, \
+                       st, P, gq);                                                       \
+    return OSCAR_OK;                                                                     \
+  }
+  OSCAR_MFMA_CASE(1, 4)
+  OSCAR_MFMA_CASE(4, 4)
+  OSCAR_MFMA_CASE(1, 1)
+#undef OSCAR_MFMA_CASE
+  return OSCAR_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+// Launches the matrix-core partial pass when the configuration is one it is built for
+// (fp16 metadata; group sizes (128,32), (32,32) or (128,128)); OSCAR_ERR_UNSUPPORTED
+// tells the caller to use the generic kernel.
+int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st) {
+  const DecodeParams& P = *reinterpret_cast<const DecodeParams*>(params);
+  if (P.c.cfg.meta_dtype != OSCAR_F16) return OSCAR_ERR_UNSUPPORTED;
+  const char* force = getenv("OSCAR_DECODE_PATH");
+  if (force && force[0] == 'g') return OSCAR_ERR_UNSUPPORTED;  // "generic"
+  if (P.g.bits == 2)
+    return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st) : launch_groups<2, 2>(P, gq, grid, st);
+  if (P.g.bits == 4)
+    return gq <= 4 ? launch_groups<4, 1>(P, gq, grid, st) : launch_groups<4, 2>(P, gq, grid, st);
+  return OSCAR_ERR_UNSUPPORTED;
+}

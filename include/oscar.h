@@ -177,7 +177,7 @@ int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t
  *   out : device, [batch][n_q_heads][head_dim], out_dtype (OSCAR_F32 or io_dtype)
  *   softmax_scale : <= 0 means 1/sqrt(head_dim)
  *   max_seq_len_hint : upper bound on seq_lens[] (>= 1); sizes the launch
- *   num_splits : split-K factor over the sequence, 0 = oscar_decode_auto_splits
+ *   num_splits : split-K factor over the sequence (<= 512), 0 = oscar_decode_auto_splits
  *   workspace  : device scratch of at least oscar_decode_workspace_bytes(...)
  * A sequence with seq_lens[b] == 0 yields zeros. */
 int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_t out_dtype,

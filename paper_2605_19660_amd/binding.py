@@ -19,7 +19,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP = 0, 
 APPEND_EAGER = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liboscar_hip.so")
+# OSCAR_HIP_LIB points at an alternative build of the same library (profiling variants)
+LIB_PATH = os.environ.get("OSCAR_HIP_LIB") or os.path.join(_HERE, "liboscar_hip.so")
 
 EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_auto_splits", "oscar_decode_workspace_bytes", "oscar_quantize_append",

@@ -227,7 +227,7 @@ extern "C" int oscar_bf16_decode_attn(const void* q, const void* k, const void* 
                                       void* stream) {
   if (!q || !k || !v || !out) return OSCAR_ERR_INVALID_ARG;
   if (batch <= 0 || kv_stride_tokens <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 ||
-      n_q_heads % n_kv_heads != 0 || num_splits < 0 || max_seq_len_hint < 0)
+      n_q_heads % n_kv_heads != 0 || num_splits < 0 || num_splits > 512 || max_seq_len_hint < 0)
     return OSCAR_ERR_INVALID_ARG;
   if (dtype != OSCAR_BF16 && dtype != OSCAR_F16) return OSCAR_ERR_UNSUPPORTED;
   if (out_dtype != OSCAR_F32 && out_dtype != dtype) return OSCAR_ERR_INVALID_ARG;

@@ -290,20 +290,45 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
 
 // Reduce pass shared with the 16-bit comparator: merges split partials
 // (o_s, m_s, l_s) with M = max m_s, out = sum o_s 2^(m_s-M) / sum l_s 2^(m_s-M).
+// One block of 128 threads per (sequence, query head); the split statistics are fetched
+// by one thread each, so no thread walks a chain of dependent loads.
 __global__ __launch_bounds__(128) void oscar_decode_reduce_kernel(const float* ws, void* out,
                                                                   int num_splits, int out_dtype) {
+  __shared__ float s_w[512];   // weight of each split (num_splits <= 512)
+  __shared__ float s_red[4];
   const size_t unit = (size_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
   const int c = threadIdx.x;
   const float* rec = ws + unit * num_splits * WS_STRIDE;
-  float M = -INFINITY;
-  for (int s = 0; s < num_splits; ++s) M = fmaxf(M, rec[(size_t)s * WS_STRIDE + D]);
-  float L = 0.0f, acc = 0.0f;
-  for (int s = 0; s < num_splits; ++s) {
+  // pass 1: M
+  float mloc = -INFINITY;
+  for (int s = c; s < num_splits; s += 128) mloc = fmaxf(mloc, rec[(size_t)s * WS_STRIDE + D]);
+  mloc = wave_max(mloc);
+  if ((c & 63) == 0) s_red[c >> 6] = mloc;
+  __syncthreads();
+  const float M = fmaxf(s_red[0], s_red[1]);
+  // pass 2: weights and L
+  float lloc = 0.0f;
+  for (int s = c; s < num_splits; s += 128) {
     const float m = rec[(size_t)s * WS_STRIDE + D];
     const float w = (m == -INFINITY) ? 0.0f : exp2f(m - M);
-    L += rec[(size_t)s * WS_STRIDE + D + 1] * w;
-    acc += rec[(size_t)s * WS_STRIDE + c] * w;
+    s_w[s] = w;
+    lloc += rec[(size_t)s * WS_STRIDE + D + 1] * w;
   }
+  lloc = wave_sum(lloc);
+  if ((c & 63) == 0) s_red[2 + (c >> 6)] = lloc;
+  __syncthreads();
+  const float L = s_red[2] + s_red[3];
+  // pass 3: weighted sum of the partial outputs, four independent loads in flight
+  float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+  int s = 0;
+  for (; s + 4 <= num_splits; s += 4) {
+    a0 = fmaf(rec[(size_t)(s + 0) * WS_STRIDE + c], s_w[s + 0], a0);
+    a1 = fmaf(rec[(size_t)(s + 1) * WS_STRIDE + c], s_w[s + 1], a1);
+    a2 = fmaf(rec[(size_t)(s + 2) * WS_STRIDE + c], s_w[s + 2], a2);
+    a3 = fmaf(rec[(size_t)(s + 3) * WS_STRIDE + c], s_w[s + 3], a3);
+  }
+  for (; s < num_splits; ++s) a0 = fmaf(rec[(size_t)s * WS_STRIDE + c], s_w[s], a0);
+  const float acc = (a0 + a1) + (a2 + a3);
   const float res = L > 0.0f ? acc / L : 0.0f;
   const size_t oi = unit * D + c;
   if (out_dtype == OSCAR_F32) reinterpret_cast<float*>(out)[oi] = res;
@@ -352,7 +377,7 @@ extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache
                                          void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_decode_cache(cache);
   if (rc != OSCAR_OK) return rc;
-  if (!q || num_splits <= 0) return OSCAR_ERR_INVALID_ARG;
+  if (!q || num_splits <= 0 || num_splits > 512) return OSCAR_ERR_INVALID_ARG;
   const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
   DecodeParams P;
@@ -381,7 +406,7 @@ extern "C" int oscar_decode_attn_reduce(const oscar_cache* cache, void* out, int
                                         size_t workspace_bytes, void* stream) {
   int rc = check_decode_cache(cache);
   if (rc != OSCAR_OK) return rc;
-  if (!out || num_splits <= 0) return OSCAR_ERR_INVALID_ARG;
+  if (!out || num_splits <= 0 || num_splits > 512) return OSCAR_ERR_INVALID_ARG;
   if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
   const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;

@@ -48,14 +48,24 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Reductions over the 16 lanes of a DPP row (= one head group): xor-1 and xor-2 inside
+// quads, then the two mirrors; every lane ends with the same bits.
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float row16_max(float v) {
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  v = fmaxf(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_mov<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_mov<0x141>(v));  // row_half_mirror
+  v = fmaxf(v, dpp_mov<0x140>(v));  // row_mirror
   return v;
 }
 __device__ __forceinline__ float row16_sum(float v) {
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) v += __shfl_xor(v, m, 64);
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  v += dpp_mov<0x140>(v);
   return v;
 }
 
@@ -136,32 +146,39 @@ template <> struct TilePair<4> {
   }
 };
 
-// Everything one wave needs of one page, in registers (prefetched one page ahead).
-template <int BITS, int NGK, int NGV> struct PageRegs {
-  TilePair<BITS> kc[4], vc[4];
+// What one wave needs of one page, in registers.  Key side and value side are separate
+// sets: each is reloaded for the next page as soon as the current page is done with it,
+// so only one copy of each is ever live.
+template <int BITS, int NGK> struct KeyRegs {
+  TilePair<BITS> kc[4];
   uint4 kd[NGK], kz[NGK];  // key Delta / zero of positions 8n..8n+7 (operand order)
   uint4 nr;                // norms of tokens 16*T+n, T = 0..7
-  uint4 vd[NGV], vz[NGV];  // value Delta / zero of the same tokens
-
   __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane) {
     const int n = lane & 15, q4 = lane >> 4;
     const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(P.c.k_codes) + pgi * P.g.k_codes_bytes;
-    const uint8_t* vcodes = reinterpret_cast<const uint8_t*>(P.c.v_codes) + pgi * P.g.v_codes_bytes;
     const uint8_t* kmeta = reinterpret_cast<const uint8_t*>(P.c.k_meta) + pgi * P.g.k_meta_bytes;
     const uint8_t* knorm = reinterpret_cast<const uint8_t*>(P.c.k_norms) + pgi * P.g.k_norms_bytes;
-    const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
     constexpr int PB = 2 * chunk_bytes(BITS);  // bytes of a lane's tile pair
 #pragma unroll
-    for (int tp = 0; tp < 4; ++tp) {
-      kc[tp].load(kcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
-      vc[tp].load(vcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
-    }
+    for (int tp = 0; tp < 4; ++tp) kc[tp].load(kcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
 #pragma unroll
     for (int g = 0; g < NGK; ++g) {
       kd[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)(g * D + 8 * n) * 2);
       kz[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)((NGK + g) * D + 8 * n) * 2);
     }
     nr = *reinterpret_cast<const uint4*>(knorm + (size_t)(8 * n) * 2);
+  }
+};
+template <int BITS, int NGV> struct ValRegs {
+  TilePair<BITS> vc[4];
+  uint4 vd[NGV], vz[NGV];  // value Delta / zero of tokens 16*T+n
+  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane) {
+    const int n = lane & 15, q4 = lane >> 4;
+    const uint8_t* vcodes = reinterpret_cast<const uint8_t*>(P.c.v_codes) + pgi * P.g.v_codes_bytes;
+    const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
+    constexpr int PB = 2 * chunk_bytes(BITS);
+#pragma unroll
+    for (int tp = 0; tp < 4; ++tp) vc[tp].load(vcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
       vd[g] = *reinterpret_cast<const uint4*>(vmeta + (size_t)(g * R + 8 * n) * 2);
@@ -169,6 +186,16 @@ template <int BITS, int NGK, int NGV> struct PageRegs {
     }
   }
 };
+
+__device__ __forceinline__ float max8_halves(const uint4& r) {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  h2 a = __builtin_bit_cast(h2, r.x), b = __builtin_bit_cast(h2, r.y);
+  h2 c = __builtin_bit_cast(h2, r.z), d = __builtin_bit_cast(h2, r.w);
+  a = __builtin_elementwise_max(a, b);
+  c = __builtin_elementwise_max(c, d);
+  a = __builtin_elementwise_max(a, c);
+  return fmaxf((float)a[0], (float)a[1]);
+}
 
 // rows of the 16-row operand tile: head h -> hi row 4*(h%4) + 2*(h/4), lo row + 1, so the
 // accumulator lane group q4 (rows 4*q4..4*q4+3) owns heads q4 (slot 0) and q4+4 (slot 1).
@@ -178,10 +205,12 @@ template <int BITS, int HP, int NGK, int NGV>
 __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   constexpr int TPG = 8 / NGK;  // token tiles per key group
   constexpr int CPG = 8 / NGV;  // channel tiles per value group
+  constexpr int TABW = D + 8;   // operand table row stride in halves
 
   __shared__ __align__(16) float s_q[OSCAR_MAX_GQA][D];
-  __shared__ __align__(16) _Float16 s_A[4][16][D];   // per wave: (Q_h Delta_k) hi/lo rows
-  __shared__ __align__(16) _Float16 s_P[4][16][D];   // per wave: (p Delta_v) hi/lo rows
+  // rows padded by 16 bytes: the 16-byte operand reads of lanes n = 0..7 hit 8 different banks
+  __shared__ __align__(16) _Float16 s_A[4][16][TABW];   // per wave: (Q_h Delta_k) hi/lo rows
+  __shared__ __align__(16) _Float16 s_P[4][16][TABW];   // per wave: (p Delta_v) hi/lo rows
   __shared__ __align__(16) float s_o[4][OSCAR_MAX_GQA][D];  // wave results for the merge
   __shared__ float s_wm[5][OSCAR_MAX_GQA], s_wl[5][OSCAR_MAX_GQA];
   // residual phase
@@ -190,7 +219,9 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   __shared__ float s_alpha[OSCAR_MAX_GQA];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // wave index as a scalar: page numbers and block-table lookups stay on the scalar unit
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, q4 = lane >> 4;
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
 
@@ -203,17 +234,34 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   const bool has_res = (split == P.num_splits - 1) && r > 0;
   const bool any_work = (pg0 < pg1) || has_res;
 
-  // zero the operand tables (rows of absent heads stay zero) and rotate the queries
-  for (int i = tid; i < 4 * 16 * D / 2; i += 256) {
+  // Start the memory chain first (block table -> first page), then rotate the queries
+  // while those loads are in flight.
+
+  // zero the operand tables (rows of absent heads stay zero)
+  for (int i = tid; i < 4 * 16 * TABW / 2; i += 256) {
     reinterpret_cast<uint32_t*>(&s_A[0][0][0])[i] = 0u;
     reinterpret_cast<uint32_t*>(&s_P[0][0][0])[i] = 0u;
   }
+  // Q_h = H(q)/sqrt(128) * scale*log2(e): wave w rotates heads w and w+4 on its own; a lane
+  // holds channels (lane, lane+64): stage 64 in registers, stages 1..32 across lanes.
   if (any_work) {
-    rotate_queries(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * gq) * D, P.c.cfg.io_dtype,
-                   P.qk_scale_log2, tid, gq);
-  } else {
-    __syncthreads();
+    for (int h = wave; h < gq; h += 4) {
+      const size_t qb = ((size_t)b * Hq + (size_t)kvh * gq + h) * D;
+      float x0 = load_io(P.q, qb + lane, P.c.cfg.io_dtype);
+      float x1 = load_io(P.q, qb + lane + 64, P.c.cfg.io_dtype);
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) {
+        const float y0 = __shfl_xor(x0, m, 64), y1 = __shfl_xor(x1, m, 64);
+        const bool up = (lane & m) != 0;
+        x0 = up ? y0 - x0 : x0 + y0;
+        x1 = up ? y1 - x1 : x1 + y1;
+      }
+      const float c = 0.08838834764831845f * P.qk_scale_log2;
+      s_q[h][lane] = (x0 + x1) * c;
+      s_q[h][lane + 64] = (x0 - x1) * c;
+    }
   }
+  __syncthreads();
 
   // ---- per-lane constants ----
   // writer role for the key operand: positions 8n..8n+7 of heads q4 (+4)
@@ -258,76 +306,96 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   for (int ct = 0; ct < 8; ++ct) O[ct] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
   int xv_cur = 0;
 
-  _Float16(*A_tab)[D] = s_A[wave];
-  _Float16(*P_tab)[D] = s_P[wave];
+  _Float16(*A_tab)[TABW] = s_A[wave];
+  _Float16(*P_tab)[TABW] = s_P[wave];
 
-  PageRegs<BITS, NGK, NGV> cur;
-  int pg = pg0 + wave;
-  if (pg < pg1) {
-    const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + pg];
-    cur.load(P, (size_t)phys * Hkv + kvh, lane);
+  KeyRegs<BITS, NGK> kr;
+  ValRegs<BITS, NGV> vr;
+  // Block-table entries of this wave's pages (pg0 + wave + 4*it) live in a register, one
+  // per lane, 64 iterations at a time: the page loop itself issues no dependent lookups.
+  const int32_t* table = P.c.block_table + (size_t)b * P.c.max_pages_per_seq;
+  const int pg_first = pg0 + wave;
+  auto load_table = [&](int it0) -> int {
+    const int idx = pg_first + 4 * (it0 + lane);
+    return idx < pg1 ? table[idx] : 0;
+  };
+  int tab = load_table(0);
+  if (pg_first < pg1) {
+    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
+    kr.load(P, pgi, lane);
+    vr.load(P, pgi, lane);
   }
-  for (; pg < pg1; pg += 4) {
-    PageRegs<BITS, NGK, NGV> nxt;
+  int it = 0;
+  for (int pg = pg_first; pg < pg1; pg += 4, ++it) {
     const bool has_next = pg + 4 < pg1;
+    size_t next_pgi = 0;
     if (has_next) {
-      const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + pg + 4];
-      nxt.load(P, (size_t)phys * Hkv + kvh, lane);
+      if (((it + 1) & 63) == 0) tab = load_table(it + 1);
+      next_pgi = (size_t)__builtin_amdgcn_readlane(tab, (it + 1) & 63) * Hkv + kvh;
     }
-
-    // token norms of this lane's 8 tokens
-    float nt[8];
-    halves_to_f32(cur.nr, nt);
 
     // ---- q K^T ----
     float S[HP][8];
+    {
+      float nt[8];
+      halves_to_f32(kr.nr, nt);
 #pragma unroll
-    for (int g = 0; g < NGK; ++g) {
-      float dk[8], zk[8];
-      halves_to_f32(cur.kd[g], dk);
-      halves_to_f32(cur.kz[g], zk);
-      float bias[HP];
+      for (int g = 0; g < NGK; ++g) {
+        float dk[8], zk[8];
+        halves_to_f32(kr.kd[g], dk);
+        halves_to_f32(kr.kz[g], zk);
+        float bias[HP];
 #pragma unroll
-      for (int s = 0; s < HP; ++s) {
-        float a[8], bp = 0.0f;
+        for (int s = 0; s < HP; ++s) {
+          float a[8], bp = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          a[i] = qs[s][i] * dk[i];
-          bp = fmaf(qr[s][i] * dk[i], zk[i], bp);
+          for (int i = 0; i < 8; ++i) {
+            a[i] = qs[s][i] * dk[i];
+            bp = fmaf(qr[s][i] * dk[i], zk[i], bp);
+          }
+          bias[s] = row16_sum(bp);
+          uint4 hi, lo;
+          split_hi_lo(a, hi, lo);
+          const int h = q4 + 4 * s;
+          if (h < gq) {
+            *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
+            *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
+          }
         }
-        bias[s] = row16_sum(bp);
-        uint4 hi, lo;
-        split_hi_lo(a, hi, lo);
-        const int h = q4 + 4 * s;
-        if (h < gq) {
-          *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
-          *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
-        }
-      }
-      wave_lds_fence();
-      half8 areg[4];
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        areg[kk] = *reinterpret_cast<const half8*>(&A_tab[n][32 * q4 + 8 * kk]);
-      wave_lds_fence();
-#pragma unroll
-      for (int tt = 0; tt < TPG; ++tt) {
-        const int T = g * TPG + tt;
-        u32x4 bop[4];
-        cur.kc[T >> 1].chunk(T & 1).operands(bop);
-        float4v acc = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
+        wave_lds_fence();
+        half8 areg[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(areg[kk], __builtin_bit_cast(half8, bop[kk]),
-                                                       acc, 0, 0, 0);
+          areg[kk] = *reinterpret_cast<const half8*>(&A_tab[n][32 * q4 + 8 * kk]);
+        wave_lds_fence();
 #pragma unroll
-        for (int s = 0; s < HP; ++s)
-          S[s][T] = nt[T] * fmaf(acc[2 * s] + acc[2 * s + 1], ps[s], -bias[s]);
+        for (int tt = 0; tt < TPG; tt += 2) {
+          // two token tiles at a time: independent accumulators keep the MFMA pipe busy
+          const int T = g * TPG + tt;
+          u32x4 b0[4], b1[4];
+          kr.kc[T >> 1].chunk(0).operands(b0);
+          kr.kc[T >> 1].chunk(1).operands(b1);
+          float4v acc0 = (float4v){0.0f, 0.0f, 0.0f, 0.0f}, acc1 = acc0;
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                areg[kk], __builtin_bit_cast(half8, b0[kk]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                areg[kk], __builtin_bit_cast(half8, b1[kk]), acc1, 0, 0, 0);
+          }
+#pragma unroll
+          for (int s = 0; s < HP; ++s) {
+            S[s][T] = nt[T] * fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]);
+            S[s][T + 1] = nt[T + 1] * fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]);
+          }
+        }
       }
     }
+    // the key registers are free: fetch the next page's key side behind the value work
+    if (has_next) kr.load(P, next_pgi, lane);
 
     // ---- online softmax (per head slot; the 16 lanes of a group share a head) ----
-    float p[HP][8], alpha[HP];
+    float alpha[HP];
     bool rescale = false;
 #pragma unroll
     for (int s = 0; s < HP; ++s) {
@@ -341,22 +409,17 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       float sum = 0.0f;
 #pragma unroll
       for (int T = 0; T < 8; ++T) {
-        p[s][T] = __builtin_amdgcn_exp2f(S[s][T] - m_new);
-        sum += p[s][T];
+        S[s][T] = __builtin_amdgcn_exp2f(S[s][T] - m_new);  // S now holds p
+        sum += S[s][T];
       }
       l_run[s] = l_run[s] * alpha[s] + sum;
     }
 
-    // ---- page scale of the value operand: Delta_v * 2^xv < 2^13 ----
-    float dv[NGV][8];
+    // ---- scale of the value operand for this page: Delta_v * 2^xv < 2^13 ----
     float dmax = 0.0f;
 #pragma unroll
-    for (int g = 0; g < NGV; ++g) {
-      halves_to_f32(cur.vd[g], dv[g]);
-#pragma unroll
-      for (int T = 0; T < 8; ++T) dmax = fmaxf(dmax, dv[g][T]);
-    }
-    dmax = wave_max(dmax);
+    for (int g = 0; g < NGV; ++g) dmax = fmaxf(dmax, max8_halves(vr.vd[g]));
+    dmax = row16_max(dmax);   // the 16 lanes of a head group cover all 128 tokens
     int exv = 0;
     (void)frexpf(dmax, &exv);
     if (!(dmax > 0.0f) || isinf(dmax)) exv = 0;
@@ -382,22 +445,20 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     xv_cur = xv;
 
     // ---- P V, one value group at a time through the wave's LDS table ----
-    float pt[HP][8];
-#pragma unroll
-    for (int s = 0; s < HP; ++s)
-#pragma unroll
-      for (int T = 0; T < 8; ++T) pt[s][T] = ldexpf(p[s][T] * vsc0[T], xv);
+    const float pscale = ldexpf(1.0f, xv);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
-      float zv[8];
-      halves_to_f32(cur.vz[g], zv);
+      float dv[8], zv[8];
+      halves_to_f32(vr.vd[g], dv);
+      halves_to_f32(vr.vz[g], zv);
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
         float a[8], acc_b = 0.0f;
 #pragma unroll
         for (int T = 0; T < 8; ++T) {
-          a[T] = pt[s][T] * dv[g][T];
-          acc_b = fmaf(p[s][T] * dv[g][T], zv[T], acc_b);
+          const float pd = S[s][T] * dv[T];
+          a[T] = pd * (vsc0[T] * pscale);
+          acc_b = fmaf(pd, zv[T], acc_b);
         }
         bv[s][g] += acc_b;
         uint4 hi, lo;
@@ -415,17 +476,21 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
         preg[kk] = *reinterpret_cast<const half8*>(&P_tab[n][8 * (4 * kk + q4)]);
       wave_lds_fence();
 #pragma unroll
-      for (int cc = 0; cc < CPG; ++cc) {
+      for (int cc = 0; cc < CPG; cc += 2) {
         const int ct = g * CPG + cc;
-        u32x4 bop[4];
-        cur.vc[ct >> 1].chunk(ct & 1).operands(bop);
+        u32x4 b0[4], b1[4];
+        vr.vc[ct >> 1].chunk(0).operands(b0);
+        vr.vc[ct >> 1].chunk(1).operands(b1);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(preg[kk], __builtin_bit_cast(half8, bop[kk]),
-                                                         O[ct], 0, 0, 0);
+        for (int kk = 0; kk < 4; ++kk) {
+          O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+              preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct], 0, 0, 0);
+          O[ct + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+              preg[kk], __builtin_bit_cast(half8, b1[kk]), O[ct + 1], 0, 0, 0);
+        }
       }
     }
-    if (has_next) cur = nxt;
+    if (has_next) vr.load(P, next_pgi, lane);
   }
 
   // ---- wave results -> LDS ----

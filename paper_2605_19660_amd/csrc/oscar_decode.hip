@@ -261,10 +261,17 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
 #pragma unroll
       for (int h = 0; h < GQ; ++h) o[h] *= s_alpha[h];
       const int t_end = min(r, th * 64 + 64);
-      for (int t = th * 64; t < t_end; ++t) {
-        const float wv = load_io(P.c.res_v, (rb + t) * D + ch, P.c.cfg.io_dtype);
+      // 16 independent loads in flight per batch (positions past the end carry p = 0)
+      for (int t0 = th * 64; t0 < t_end; t0 += 16) {
+        float wv[16];
 #pragma unroll
-        for (int h = 0; h < GQ; ++h) o[h] = fmaf(s_S[h][chunk_order(BITS, t)], wv, o[h]);
+        for (int i = 0; i < 16; ++i)
+          wv[i] = (t0 + i < t_end) ? load_io(P.c.res_v, (rb + t0 + i) * D + ch, P.c.cfg.io_dtype) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+          for (int h = 0; h < GQ; ++h)
+            o[h] = fmaf(s_S[h][chunk_order(BITS, t0 + i)], wv[i], o[h]);
       }
     }
     __syncthreads();

@@ -212,6 +212,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   __shared__ __align__(16) _Float16 s_A[4][16][TABW];   // per wave: (Q_h Delta_k) hi/lo rows
   __shared__ __align__(16) _Float16 s_P[4][16][TABW];   // per wave: (p Delta_v) hi/lo rows
   __shared__ __align__(16) float s_o[4][OSCAR_MAX_GQA][D];  // wave results for the merge
+  __shared__ __align__(16) float s_ores[OSCAR_MAX_GQA][D];  // residual-window result
   __shared__ float s_wm[5][OSCAR_MAX_GQA], s_wl[5][OSCAR_MAX_GQA];
   // residual phase
   __shared__ float s_norm[R];
@@ -262,6 +263,95 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     }
   }
   __syncthreads();
+
+  // ---- residual tokens (last split): plain-ALU attention over fp16 K_u and raw V, done
+  // up front so its load latencies overlap the first page fetch; result parked in LDS ----
+  const int tok = tid >> 1, half = tid & 1;  // logits: (token, channel half)
+  const int ch = tid >> 1, th = tid & 1;     // values: (channel, token half)
+  if (tid < OSCAR_MAX_GQA) {
+    s_wm[4][tid] = -INFINITY;
+    s_wl[4][tid] = 0.0f;
+  }
+  if (has_res) {
+    const int mb = P.g.meta_bytes;
+    const size_t rb = ((size_t)b * Hkv + kvh) * R;
+    const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
+    if (tid < R) s_norm[tid] = tid < r ? load_meta(P.c.res_norm, rb + tid, mb) : 0.0f;
+    __syncthreads();
+    {
+      float acc[OSCAR_MAX_GQA];
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) acc[h] = 0.0f;
+      if (tok < r) {
+        const uint4* kp = reinterpret_cast<const uint4*>(rk + (size_t)tok * D + half * 64);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float kv[8];
+          halves_to_f32(kp[i], kv);
+          const int j = half * 64 + i * 8;
+#pragma unroll
+          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+            if (h < gq) {
+              const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
+              const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
+              acc[h] = fmaf(qa.x, kv[0], acc[h]);
+              acc[h] = fmaf(qa.y, kv[1], acc[h]);
+              acc[h] = fmaf(qa.z, kv[2], acc[h]);
+              acc[h] = fmaf(qa.w, kv[3], acc[h]);
+              acc[h] = fmaf(qb.x, kv[4], acc[h]);
+              acc[h] = fmaf(qb.y, kv[5], acc[h]);
+              acc[h] = fmaf(qb.z, kv[6], acc[h]);
+              acc[h] = fmaf(qb.w, kv[7], acc[h]);
+            }
+          }
+        }
+      }
+      const float nrm = s_norm[tok];
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
+        if (half == 0 && h < gq) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
+      }
+    }
+    __syncthreads();
+    for (int h = wave; h < gq; h += 4) {
+      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
+      const float m_new = wave_max(fmaxf(s0, s1));
+      const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
+      const float sum = wave_sum(p0 + p1);
+      s_S[h][lane] = p0;
+      s_S[h][lane + 64] = p1;
+      if (lane == 0) {
+        s_wm[4][h] = m_new;
+        s_wl[4][h] = sum;
+      }
+    }
+    __syncthreads();
+    {
+      float o_res[OSCAR_MAX_GQA];
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] = 0.0f;
+      const int t_end = min(r, th * 64 + 64);
+      // 16 independent loads in flight per batch (positions past the end carry p = 0)
+      for (int t0 = th * 64; t0 < t_end; t0 += 16) {
+        float wv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          wv[i] = (t0 + i < t_end) ? load_io(P.c.res_v, (rb + t0 + i) * D + ch, P.c.cfg.io_dtype) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+          for (int h = 0; h < OSCAR_MAX_GQA; ++h)
+            if (h < gq) o_res[h] = fmaf(s_S[h][t0 + i], wv[i], o_res[h]);
+      }
+      // both token halves of a channel sit in neighbouring lanes
+#pragma unroll
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+        const float tot = o_res[h] + __shfl_xor(o_res[h], 1, 64);
+        if (th == 0 && h < gq) s_ores[h][ch] = tot;
+      }
+    }
+  }
 
   // ---- per-lane constants ----
   // writer role for the key operand: positions 8n..8n+7 of heads q4 (+4)
@@ -515,87 +605,8 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     }
   }
 
-  // ---- residual tokens (last split): plain-ALU attention over fp16 K_u and raw V ----
-  const int tok = tid >> 1, half = tid & 1;  // logits: (token, channel half)
-  const int ch = tid >> 1, th = tid & 1;     // values: (channel, token half)
-  float o_res[OSCAR_MAX_GQA];
-#pragma unroll
-  for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] = 0.0f;
-  if (tid < OSCAR_MAX_GQA) {
-    s_wm[4][tid] = -INFINITY;
-    s_wl[4][tid] = 0.0f;
-  }
-  if (has_res) {
-    const int mb = P.g.meta_bytes;
-    const size_t rb = ((size_t)b * Hkv + kvh) * R;
-    const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
-    if (tid < R) s_norm[tid] = tid < r ? load_meta(P.c.res_norm, rb + tid, mb) : 0.0f;
-    __syncthreads();
-    {
-      float acc[OSCAR_MAX_GQA];
-#pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) acc[h] = 0.0f;
-      if (tok < r) {
-        const uint4* kp = reinterpret_cast<const uint4*>(rk + (size_t)tok * D + half * 64);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          float kv[8];
-          halves_to_f32(kp[i], kv);
-          const int j = half * 64 + i * 8;
-#pragma unroll
-          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-            if (h < gq) {
-              const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
-              const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
-              acc[h] = fmaf(qa.x, kv[0], acc[h]);
-              acc[h] = fmaf(qa.y, kv[1], acc[h]);
-              acc[h] = fmaf(qa.z, kv[2], acc[h]);
-              acc[h] = fmaf(qa.w, kv[3], acc[h]);
-              acc[h] = fmaf(qb.x, kv[4], acc[h]);
-              acc[h] = fmaf(qb.y, kv[5], acc[h]);
-              acc[h] = fmaf(qb.z, kv[6], acc[h]);
-              acc[h] = fmaf(qb.w, kv[7], acc[h]);
-            }
-          }
-        }
-      }
-      const float nrm = s_norm[tok];
-#pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
-        if (half == 0 && h < gq) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
-      }
-    }
-    __syncthreads();
-    for (int h = wave; h < gq; h += 4) {
-      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
-      const float m_new = wave_max(fmaxf(s0, s1));
-      const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
-      const float sum = wave_sum(p0 + p1);
-      s_S[h][lane] = p0;
-      s_S[h][lane + 64] = p1;
-      if (lane == 0) {
-        s_wm[4][h] = m_new;
-        s_wl[4][h] = sum;
-      }
-    }
-    __syncthreads();
-    {
-      const int t_end = min(r, th * 64 + 64);
-      for (int t = th * 64; t < t_end; ++t) {
-        const float wv = load_io(P.c.res_v, (rb + t) * D + ch, P.c.cfg.io_dtype);
-#pragma unroll
-        for (int h = 0; h < OSCAR_MAX_GQA; ++h)
-          if (h < gq) o_res[h] = fmaf(s_S[h][t], wv, o_res[h]);
-      }
-    }
-  }
-  __syncthreads();
-
   // ---- merge the 4 wave states and the residual state, write the split's record ----
-  // o_res holds this thread's token half of the residual sum; add the partner's
-#pragma unroll
-  for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] += __shfl_xor(o_res[h], 1, 64);
+  __syncthreads();
 #pragma unroll
   for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
     if (h < gq && (h & 1) == th) {
@@ -604,7 +615,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
       float acc = 0.0f;
       if (M != -INFINITY) {
-        acc = o_res[h] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
+        if (s_wm[4][h] != -INFINITY) acc = s_ores[h][ch] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
           if (s_wm[w][h] != -INFINITY) acc += s_o[w][h][ch] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);

@@ -111,7 +111,11 @@ typedef struct oscar_config {
  * (seq_lens[b]-res_lens[b])/R whole pages. A fresh cache has both arrays zeroed.
  * dev_status (may be NULL): a device int32 the kernels set to OSCAR_ERR_CAPACITY
  * when a sequence would need more than max_pages_per_seq pages; that append is
- * dropped for that sequence. */
+ * dropped for that sequence.
+ * tickets (may be NULL): a device int32[1], zeroed once by the caller. With it the last
+ * workgroup of oscar_quantize_append to finish also advances seq_lens / res_lens (one
+ * launch) and leaves the ticket zero again; without it the length update is a second,
+ * tiny launch. */
 typedef struct oscar_cache {
   oscar_config cfg;
   int32_t batch;
@@ -124,13 +128,14 @@ typedef struct oscar_cache {
   int32_t *seq_lens;    /* [batch] */
   int32_t *res_lens;    /* [batch] */
   int32_t *dev_status;  /* [1] or NULL */
+  int32_t *tickets;     /* [1] zero-initialised, or NULL */
 } oscar_cache;
 
 /* Byte sizes of every pool for `batch` sequences and `num_pages` physical pages. */
 typedef struct oscar_pool_sizes {
   size_t k_codes, k_meta, k_norms, v_codes, v_meta; /* whole pools */
   size_t res_k, res_v, res_norm;
-  size_t block_table, seq_lens, res_lens;
+  size_t block_table, seq_lens, res_lens, tickets;
   size_t page_bytes_per_kv_head;  /* packed bytes of one page of one kv head (all five pools) */
   size_t bytes_per_token_kv_head; /* = page_bytes_per_kv_head / page_size */
 } oscar_pool_sizes;

@@ -45,13 +45,13 @@ class CCache(C.Structure):
                 ("num_pages", C.c_int32), ("reserved_", C.c_int32)] + [
         (n, C.c_void_p) for n in ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k",
                                   "res_v", "res_norm", "block_table", "seq_lens", "res_lens",
-                                  "dev_status")]
+                                  "dev_status", "tickets")]
 
 
 class CPoolSizes(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in (
         "k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
-        "block_table", "seq_lens", "res_lens", "page_bytes_per_kv_head",
+        "block_table", "seq_lens", "res_lens", "tickets", "page_bytes_per_kv_head",
         "bytes_per_token_kv_head")]
 
 
@@ -155,7 +155,7 @@ class Cache:
     range(num_pages)) to scatter logical pages over physical ones."""
 
     def __init__(self, cfg: Config, batch: int, max_pages_per_seq: int, device="cuda",
-                 num_pages: int | None = None, page_perm=None):
+                 num_pages: int | None = None, page_perm=None, fused: bool = True):
         import torch
         self.cfg, self.batch, self.max_pages_per_seq = cfg, batch, max_pages_per_seq
         self.num_pages = num_pages if num_pages is not None else batch * max_pages_per_seq
@@ -177,12 +177,15 @@ class Cache:
         self.seq_lens = torch.zeros(batch, dtype=torch.int32, device=self.device)
         self.res_lens = torch.zeros(batch, dtype=torch.int32, device=self.device)
         self.dev_status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.tickets = torch.zeros(int(sz.tickets) // 4, dtype=torch.int32, device=self.device)
+        self.fused = fused
         self._c = CCache()
         self._c.cfg = cfg.c()
         self._c.batch, self._c.max_pages_per_seq, self._c.num_pages = batch, max_pages_per_seq, self.num_pages
         for n in ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
                   "block_table", "seq_lens", "res_lens", "dev_status"):
             setattr(self._c, n, getattr(self, n).data_ptr())
+        self._c.tickets = self.tickets.data_ptr() if fused else None
 
     @property
     def c(self) -> CCache:

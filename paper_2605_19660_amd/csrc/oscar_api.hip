@@ -69,6 +69,7 @@ extern "C" int oscar_cache_sizes(const oscar_config* cfg, int32_t batch, int32_t
   out->block_table = (size_t)batch * max_pages_per_seq * sizeof(int32_t);
   out->seq_lens = (size_t)batch * sizeof(int32_t);
   out->res_lens = (size_t)batch * sizeof(int32_t);
+  out->tickets = sizeof(int32_t);
   out->page_bytes_per_kv_head = (size_t)g.total();
   out->bytes_per_token_kv_head = (size_t)g.total() / OSCAR_R;
   return OSCAR_OK;
@@ -92,9 +93,10 @@ extern "C" int32_t oscar_decode_auto_splits(const oscar_config* cfg, int32_t bat
     n_cu = prop.multiProcessorCount;
   const int pages = max_seq_len > 0 ? (max_seq_len + OSCAR_R - 1) / OSCAR_R : 1;
   const int units = batch * cfg->n_kv_heads;
-  // aim at ~4 workgroups per CU, at least 2 pages per split
-  int splits = (4 * n_cu + units - 1) / units;
-  const int max_by_pages = pages / 2 > 0 ? pages / 2 : 1;
+  // two workgroups (8 waves) per CU are resident at a time and every wave wants at least
+  // two pages: aim at one round of workgroups
+  int splits = (2 * n_cu) / units;
+  const int max_by_pages = pages / 8 > 0 ? pages / 8 : 1;
   if (splits > max_by_pages) splits = max_by_pages;
   if (splits < 1) splits = 1;
   if (splits > 512) splits = 512;

@@ -379,9 +379,9 @@ static int check_decode_cache(const oscar_cache* cache) {
   return OSCAR_OK;
 }
 
-extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache,
-                                         float softmax_scale, int32_t num_splits,
-                                         void* workspace, size_t workspace_bytes, void* stream) {
+static int launch_partial(const void* q, const oscar_cache* cache, void* out, int32_t out_dtype,
+                          float softmax_scale, int32_t num_splits, void* workspace,
+                          size_t workspace_bytes, void* stream) {
   int rc = check_decode_cache(cache);
   if (rc != OSCAR_OK) return rc;
   if (!q || num_splits <= 0 || num_splits > 512) return OSCAR_ERR_INVALID_ARG;
@@ -389,14 +389,14 @@ extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
   DecodeParams P;
   P.q = q;
-  P.out = nullptr;
+  P.out = out;
   P.ws = reinterpret_cast<float*>(workspace);
   P.c = *cache;
   P.g = make_geom(cache->cfg.bits, cache->cfg.k_group, cache->cfg.v_group, cache->cfg.meta_dtype);
   P.num_splits = num_splits;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 0.08838834764831845f;
   P.qk_scale_log2 = scale * 1.4426950408889634f;
-  P.out_dtype = OSCAR_F32;
+  P.out_dtype = out_dtype;
   const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
   dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -406,6 +406,13 @@ extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache
   if (rc != OSCAR_OK) return rc;
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
   return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache,
+                                         float softmax_scale, int32_t num_splits,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  return launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
+                        workspace_bytes, stream);
 }
 
 extern "C" int oscar_decode_attn_reduce(const oscar_cache* cache, void* out, int32_t out_dtype,
@@ -434,8 +441,8 @@ extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* 
   if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
   if (num_splits == 0)
     num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
-  rc = oscar_decode_attn_partial(q, cache, softmax_scale, num_splits, workspace, workspace_bytes,
-                                 stream);
+  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
+                      workspace_bytes, stream);
   if (rc != OSCAR_OK) return rc;
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
                                   stream);

@@ -219,14 +219,15 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   const int Hkv = P.c.cfg.n_kv_heads;
 
   const SeqPlan sp = plan_sequence(P, b);
-  if (sp.n <= 0) return;
+  do {  // one pass; "break" = this workgroup has nothing (more) to do
+  if (sp.n <= 0) break;
   if (!sp.ok) {
     if (tid == 0 && blk == 0 && kvh == 0 && P.c.dev_status) *P.c.dev_status = OSCAR_ERR_CAPACITY;
-    return;
+    break;
   }
   const bool do_block = blk < sp.nq;
   const bool do_tail = (blk == 0);
-  if (!do_block && !do_tail) return;
+  if (!do_block && !do_tail) break;
 
   const IO* knew = reinterpret_cast<const IO*>(P.k);
   const IO* vnew = reinterpret_cast<const IO*>(P.v);
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       }
     }
   }
-  if (!do_block) return;
+  if (!do_block) break;
 
   // ---- phase 3: quantize the block held in registers ----
   const int logical_page = sp.packed_pages + blk;
@@ -457,6 +458,30 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     }
     if (tid < R) o_knorm[tid] = s_norm[tid];
   }
+  } while (false);
+
+  // ---- length update, folded in: the last workgroup to finish (every other one has read
+  // seq_lens / res_lens by then) advances the lengths of all sequences ----
+  if (P.c.tickets) {
+    __shared__ int s_last;
+    __syncthreads();
+    if (tid == 0) {
+      __threadfence();
+      const int total = (int)(gridDim.x * gridDim.y * gridDim.z);
+      s_last = (atomicAdd(&P.c.tickets[0], 1) == total - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (s_last) {
+      for (int bb = tid; bb < P.c.batch; bb += 256) {
+        const SeqPlan q = plan_sequence(P, bb);
+        if (q.n > 0 && q.ok) {
+          P.c.seq_lens[bb] += q.n;
+          P.c.res_lens[bb] = q.tail_len;
+        }
+      }
+      if (tid == 0) P.c.tickets[0] = 0;
+    }
+  }
 }
 
 template <typename META>
@@ -492,11 +517,11 @@ int launch_meta(const AppendParams& P, dim3 grid, hipStream_t st) {
   int rc;
   if (P.c.cfg.meta_dtype == OSCAR_F16) {
     rc = launch_bits<IO, __half>(P, grid, st);
-    if (rc == OSCAR_OK)
+    if (rc == OSCAR_OK && !P.c.tickets)
       hipLaunchKernelGGL((oscar_update_lens_kernel<__half>), dim3((P.c.batch + 63) / 64), dim3(64), 0, st, P);
   } else {
     rc = launch_bits<IO, float>(P, grid, st);
-    if (rc == OSCAR_OK)
+    if (rc == OSCAR_OK && !P.c.tickets)
       hipLaunchKernelGGL((oscar_update_lens_kernel<float>), dim3((P.c.batch + 63) / 64), dim3(64), 0, st, P);
   }
   return rc;

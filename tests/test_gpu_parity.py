@@ -33,11 +33,11 @@ def to_dev(x, io):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dt).contiguous()
 
 
-def make_pair(w: synth.Workload, cap_pages, page_perm=None):
+def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True):
     ob = _ob()
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
                     w.page_size, DT[w.io_dtype], DT[w.meta_dtype])
-    g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm)
+    g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm, fused=fused)
     o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
                                  DT[w.meta_dtype]), w.batch, w.n_kv_heads, (cap_pages + 1) * w.page_size)
     return g, o
@@ -233,6 +233,36 @@ def test_capacity_and_argument_errors():
         ob.decode_attn(g, q, max_seq_len_hint=300, num_splits=4,
                        workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == ob.ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("path", ["mfma", "generic"])
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("hq,hkv,bits,kg,vg", [(8, 2, 2, 128, 32), (14, 2, 2, 32, 32),
+                                              (16, 2, 4, 128, 128), (3, 1, 4, 128, 32)])
+def test_decode_paths_and_fusion_agree_with_oracle(monkeypatch, path, fused, hq, hkv, bits, kg, vg):
+    """Matrix-core and plain-ALU partial passes, with the length update of the appends folded
+    into the append launch (ticket) or as a separate launch."""
+    import torch
+    ob = _ob()
+    monkeypatch.setenv("OSCAR_DECODE_PATH", path)
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=hq, n_kv_heads=hkv, context=128 * 6 + 100,
+                                  bits=bits, k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 10, fused=fused)
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    ob.quantize_append(g, kd[:, :700].contiguous(), vd[:, :700].contiguous(), eager=True)
+    o.append(k[:, :700], v[:, :700], eager=True)
+    for step in range(3):
+        lo, hi = 700 + 56 * step, 700 + 56 * (step + 1)
+        ob.quantize_append(g, kd[:, lo:hi].contiguous(), vd[:, lo:hi].contiguous())
+        o.append(k[:, lo:hi], v[:, lo:hi])
+        assert_cache_equal(g, o, w)
+        q = synth.make_q(w, step)
+        for splits in (1, 3):
+            out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=hi, num_splits=splits)
+            assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+    torch.cuda.synchronize()
+    assert int(g.tickets.abs().sum().item()) == 0       # every ticket handed back
 
 
 # -------------------------------------------------------------- comparator --

@@ -415,13 +415,23 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     kr.load(P, pgi, lane);
     vr.load(P, pgi, lane);
   }
-  int it = 0;
-  for (int pg = pg_first; pg < pg1; pg += 4, ++it) {
+  // Iterations come in chunks of 64 so that the table register is only reloaded between
+  // chunks; tabn (lane 0) is the first entry of the following chunk.
+  for (int it0 = 0; pg_first + 4 * it0 < pg1; it0 += 64) {
+  if (it0 > 0) tab = load_table(it0);
+  const int tabn = load_table(it0 + 64);
+  const int it_end = min(64, (pg1 - pg_first - 4 * it0 + 3) / 4);
+  // touch both registers here, so the wait for these two loads sits outside the page loop
+  // (inside it, it would also wait for every prefetch in flight)
+  asm volatile("" ::"v"(tab), "v"(tabn));
+  for (int iti = 0; iti < it_end; ++iti) {
+    const int pg = pg_first + 4 * (it0 + iti);
     const bool has_next = pg + 4 < pg1;
     size_t next_pgi = 0;
     if (has_next) {
-      if (((it + 1) & 63) == 0) tab = load_table(it + 1);
-      next_pgi = (size_t)__builtin_amdgcn_readlane(tab, (it + 1) & 63) * Hkv + kvh;
+      const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
+                                : __builtin_amdgcn_readlane(tabn, 0);
+      next_pgi = (size_t)phys * Hkv + kvh;
     }
 
     // ---- q K^T ----
@@ -581,6 +591,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       }
     }
     if (has_next) vr.load(P, next_pgi, lane);
+  }
   }
 
   // ---- wave results -> LDS ----

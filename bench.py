@@ -33,14 +33,17 @@ LLC_BYTES = 256 << 20       # Infinity Cache
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations")
     ap.add_argument("--bits", type=int, default=0, help="override bits (2|4)")
     ap.add_argument("--splits", type=int, default=0, help="override the split-K factor")
     ap.add_argument("--copies", type=int, default=0, help="override the number of cache copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of 256 MiB five times, so that a "
+                         "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE by a known size")
     return ap.parse_args()
 
 
@@ -137,32 +140,39 @@ def main():
     splits = args.splits or ob.decode_auto_splits(cfg, w.batch, w.context + total_steps)
     ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
 
-    EV_EVERY = 8   # bracket the decode kernel with events on every 8th step only
+    EV_EVERY = 5   # every 5th launch of the decode kernel carries a HIP event pair (5 is
+                   # coprime to the usual copy counts, so every cache copy gets sampled)
 
     def step(i, ev=None):
         c = caches[i % n_copies]
         ob.quantize_append(c, new_k[i], new_v[i], stream=stream)
-        if ev is not None:
-            ev[0].record(stream)
-        ob.decode_attn_partial(c, q, ws, splits, stream=stream)
-        if ev is not None:
-            ev[1].record(stream)
+        ob.decode_attn_partial(c, q, ws, splits, stream=stream, timer=ev)
         ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           if i % EV_EVERY == 0 else None for i in range(args.steps)]
+    evs = [ob.Timer() if i % EV_EVERY == 0 or args.steps < 64 else None for i in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, evs[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     us_step = wall / args.steps * 1e6
-    k_us = float(np.mean([e[0].elapsed_time(e[1]) for e in evs if e is not None])) * 1e3
+    k_us = float(np.mean([e.elapsed_us() for e in evs if e is not None]))
+    for e in evs:
+        if e is not None:
+            e.close()
     assert all(int(c.dev_status.item()) == 0 for c in caches)
     achieved = cache_bytes / (k_us * 1e-6) / 1e9
+
+    if args.calibrate_copy:
+        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)          # reads 256 MiB, writes 256 MiB per launch
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- BF16 comparator on the same logical K, V (its 1 GB+ stream is already cold) ----
     bf16 = None

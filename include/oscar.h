@@ -202,6 +202,21 @@ int oscar_decode_attn_reduce(const oscar_cache *cache, void *out, int32_t out_dt
                              int32_t num_splits, const void *workspace, size_t workspace_bytes,
                              void *stream);
 
+/* Measurement aid (not part of the method): a timer owns a pair of HIP events.
+ * oscar_decode_attn_partial_timed is oscar_decode_attn_partial with the events attached to
+ * the kernel's own dispatch (start/stop events of an extended launch), so that
+ * oscar_timer_elapsed_us returns the device time from that dispatch's start marker to its
+ * stop marker, with no other kernel in between.  oscar_timer_elapsed_us waits for the kernel; it returns
+ * OSCAR_ERR_INVALID_ARG for a timer no launch has used yet.  A timer may be reused by a
+ * later launch once its elapsed time has been read.  The caller destroys what it creates. */
+typedef struct oscar_timer oscar_timer;
+int oscar_timer_create(oscar_timer **timer);
+int oscar_timer_destroy(oscar_timer *timer);
+int oscar_timer_elapsed_us(oscar_timer *timer, float *us);
+int oscar_decode_attn_partial_timed(const void *q, const oscar_cache *cache, float softmax_scale,
+                                    int32_t num_splits, void *workspace, size_t workspace_bytes,
+                                    void *stream, oscar_timer *timer);
+
 /* 16-bit comparator: the same split-K decode attention on an uncompressed,
  * un-rotated cache (the BF16 FlashDecoding-style baseline of the paper's
  * efficiency section).

@@ -25,7 +25,8 @@ LIB_PATH = os.environ.get("OSCAR_HIP_LIB") or os.path.join(_HERE, "liboscar_hip.
 EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_auto_splits", "oscar_decode_workspace_bytes", "oscar_quantize_append",
            "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
-           "oscar_bf16_decode_attn", "oscar_debug_dump")
+           "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
+           "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed")
 
 
 class OscarError(RuntimeError):
@@ -84,6 +85,14 @@ def lib():
     L.oscar_decode_attn.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp, sz, vp]
     L.oscar_decode_attn_partial.restype = C.c_int
     L.oscar_decode_attn_partial.argtypes = [vp, C.POINTER(CCache), f32, i32, vp, sz, vp]
+    L.oscar_decode_attn_partial_timed.restype = C.c_int
+    L.oscar_decode_attn_partial_timed.argtypes = [vp, C.POINTER(CCache), f32, i32, vp, sz, vp, vp]
+    L.oscar_timer_create.restype = C.c_int
+    L.oscar_timer_create.argtypes = [C.POINTER(vp)]
+    L.oscar_timer_destroy.restype = C.c_int
+    L.oscar_timer_destroy.argtypes = [vp]
+    L.oscar_timer_elapsed_us.restype = C.c_int
+    L.oscar_timer_elapsed_us.argtypes = [vp, C.POINTER(C.c_float)]
     L.oscar_decode_attn_reduce.restype = C.c_int
     L.oscar_decode_attn_reduce.argtypes = [C.POINTER(CCache), vp, i32, i32, vp, sz, vp]
     L.oscar_bf16_decode_attn.restype = C.c_int
@@ -239,9 +248,34 @@ def decode_attn(cache: Cache, q, out=None, scale: float = 0.0, max_seq_len_hint:
     return out
 
 
+class Timer:
+    """oscar_timer: device time of one kernel launched by decode_attn_partial(timer=...)."""
+
+    def __init__(self):
+        self.handle = C.c_void_p()
+        _check(lib().oscar_timer_create(C.byref(self.handle)), "oscar_timer_create")
+
+    def elapsed_us(self) -> float:
+        us = C.c_float()
+        _check(lib().oscar_timer_elapsed_us(self.handle, C.byref(us)), "oscar_timer_elapsed_us")
+        return us.value
+
+    def close(self):
+        if self.handle:
+            lib().oscar_timer_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+
 def decode_attn_partial(cache: Cache, q, workspace, num_splits: int, scale: float = 0.0,
-                        stream=None):
-    """oscar_decode_attn_partial: first pass only (writes split partials to `workspace`)."""
+                        stream=None, timer: "Timer | None" = None):
+    """oscar_decode_attn_partial(_timed): first pass only (writes split partials to `workspace`)."""
+    if timer is not None:
+        rc = lib().oscar_decode_attn_partial_timed(q.data_ptr(), C.byref(cache.c), scale,
+                                                   num_splits, workspace.data_ptr(),
+                                                   workspace.numel(), _stream_ptr(stream),
+                                                   timer.handle)
+        _check(rc, "oscar_decode_attn_partial_timed")
+        return
     rc = lib().oscar_decode_attn_partial(q.data_ptr(), C.byref(cache.c), scale, num_splits,
                                          workspace.data_ptr(), workspace.numel(),
                                          _stream_ptr(stream))

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -134,13 +135,20 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as
 // Host-side validation shared by the entry points.
 int oscar_validate_config(const oscar_config* cfg);
 
+// the pair of events behind the measurement-aid entry points
+struct oscar_timer {
+  hipEvent_t start, stop;
+  int armed;
+};
+
 // Reduce pass of split-K decode (defined with the decode kernels).
 void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int out_dtype,
                                 int n_q_heads, int batch, hipStream_t st);
 
 // Matrix-core partial pass (params = the decode parameter block); returns
 // OSCAR_ERR_UNSUPPORTED when the configuration must take the generic kernel.
-int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st);
+int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
+                             hipEvent_t e0, hipEvent_t e1);
 
 #define OSCAR_HIP_CHECK(expr)                 \
   do {                                        \

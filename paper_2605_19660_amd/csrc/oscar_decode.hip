@@ -353,10 +353,14 @@ void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int 
 namespace {
 
 template <int BITS>
-int launch_gq(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
+int launch_gq(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipEvent_t e0,
+              hipEvent_t e1) {
   switch (gq) {
 #define OSCAR_CASE(G) \
-  case G: hipLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st, P); break;
+  case G:                                                                                  \
+    hipExtLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st, e0, \
+                          e1, 0, P);                                                       \
+    break;
     OSCAR_CASE(1) OSCAR_CASE(2) OSCAR_CASE(3) OSCAR_CASE(4)
     OSCAR_CASE(5) OSCAR_CASE(6) OSCAR_CASE(7) OSCAR_CASE(8)
 #undef OSCAR_CASE
@@ -381,10 +385,11 @@ static int check_decode_cache(const oscar_cache* cache) {
 
 static int launch_partial(const void* q, const oscar_cache* cache, void* out, int32_t out_dtype,
                           float softmax_scale, int32_t num_splits, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+                          size_t workspace_bytes, void* stream, oscar_timer* timer) {
   int rc = check_decode_cache(cache);
   if (rc != OSCAR_OK) return rc;
   if (!q || num_splits <= 0 || num_splits > 512) return OSCAR_ERR_INVALID_ARG;
+  hipEvent_t e0 = timer ? timer->start : nullptr, e1 = timer ? timer->stop : nullptr;
   const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
   DecodeParams P;
@@ -400,19 +405,66 @@ static int launch_partial(const void* q, const oscar_cache* cache, void* out, in
   const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
   dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  rc = oscar_launch_decode_mfma(&P, gq, grid, st);
+  rc = oscar_launch_decode_mfma(&P, gq, grid, st, e0, e1);
   if (rc == OSCAR_ERR_UNSUPPORTED)
-    rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st) : launch_gq<4>(P, gq, grid, st);
+    rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st, e0, e1)
+                                : launch_gq<4>(P, gq, grid, st, e0, e1);
   if (rc != OSCAR_OK) return rc;
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+  if (timer) timer->armed = 1;
   return OSCAR_OK;
+}
+
+extern "C" int oscar_timer_create(oscar_timer** timer) {
+  if (!timer) return OSCAR_ERR_INVALID_ARG;
+  oscar_timer* t = new (std::nothrow) oscar_timer;
+  if (!t) return OSCAR_ERR_HIP;
+  t->start = t->stop = nullptr;
+  t->armed = 0;
+  if (hipEventCreate(&t->start) != hipSuccess || hipEventCreate(&t->stop) != hipSuccess) {
+    if (t->start) (void)hipEventDestroy(t->start);
+    delete t;
+    (void)hipGetLastError();
+    return OSCAR_ERR_HIP;
+  }
+  *timer = t;
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_timer_destroy(oscar_timer* timer) {
+  if (!timer) return OSCAR_OK;
+  (void)hipEventDestroy(timer->start);
+  (void)hipEventDestroy(timer->stop);
+  delete timer;
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_timer_elapsed_us(oscar_timer* timer, float* us) {
+  if (!timer || !us || !timer->armed) return OSCAR_ERR_INVALID_ARG;
+  float ms = 0.0f;
+  if (hipEventSynchronize(timer->stop) != hipSuccess ||
+      hipEventElapsedTime(&ms, timer->start, timer->stop) != hipSuccess) {
+    (void)hipGetLastError();
+    return OSCAR_ERR_HIP;
+  }
+  *us = ms * 1000.0f;
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn_partial_timed(const void* q, const oscar_cache* cache,
+                                               float softmax_scale, int32_t num_splits,
+                                               void* workspace, size_t workspace_bytes,
+                                               void* stream, oscar_timer* timer) {
+  if (!timer) return OSCAR_ERR_INVALID_ARG;
+  return launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
+                        workspace_bytes, stream, timer);
 }
 
 extern "C" int oscar_decode_attn_partial(const void* q, const oscar_cache* cache,
                                          float softmax_scale, int32_t num_splits,
                                          void* workspace, size_t workspace_bytes, void* stream) {
   return launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
-                        workspace_bytes, stream);
+                        workspace_bytes, stream, nullptr);
 }
 
 extern "C" int oscar_decode_attn_reduce(const oscar_cache* cache, void* out, int32_t out_dtype,
@@ -442,7 +494,7 @@ extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* 
   if (num_splits == 0)
     num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
   rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
-                      workspace_bytes, stream);
+                      workspace_bytes, stream, nullptr);
   if (rc != OSCAR_OK) return rc;
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
                                   stream);

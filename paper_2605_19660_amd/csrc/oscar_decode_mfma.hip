@@ -187,6 +187,29 @@ template <int BITS, int NGV> struct ValRegs {
   }
 };
 
+// two neighbouring values of the caller's dtype, held raw until they are needed
+struct Raw2 {
+  uint32_t a, b;
+};
+__device__ __forceinline__ Raw2 load_raw2(const void* p, size_t idx, int dt) {
+  Raw2 r;
+  if (dt == OSCAR_F32) {
+    const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const float*>(p) + idx);
+    r.a = v.x;
+    r.b = v.y;
+  } else {
+    r.a = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(p) + idx);
+    r.b = 0u;
+  }
+  return r;
+}
+__device__ __forceinline__ float2 raw2_to_f32(const Raw2& r, int dt) {
+  if (dt == OSCAR_F32) return make_float2(__uint_as_float(r.a), __uint_as_float(r.b));
+  if (dt == OSCAR_BF16) return make_float2(__uint_as_float(r.a << 16), __uint_as_float(r.a & 0xffff0000u));
+  return make_float2(__half2float(__ushort_as_half((unsigned short)(r.a & 0xffffu))),
+                     __half2float(__ushort_as_half((unsigned short)(r.a >> 16))));
+}
+
 __device__ __forceinline__ float max8_halves(const uint4& r) {
   typedef _Float16 h2 __attribute__((ext_vector_type(2)));
   h2 a = __builtin_bit_cast(h2, r.x), b = __builtin_bit_cast(h2, r.y);
@@ -215,9 +238,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   __shared__ __align__(16) float s_ores[OSCAR_MAX_GQA][D];  // residual-window result
   __shared__ float s_wm[5][OSCAR_MAX_GQA], s_wl[5][OSCAR_MAX_GQA];
   // residual phase
-  __shared__ float s_norm[R];
   __shared__ __align__(16) float s_S[OSCAR_MAX_GQA][R];
-  __shared__ float s_alpha[OSCAR_MAX_GQA];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -232,11 +253,50 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   const int pps = (n_pages + P.num_splits - 1) / P.num_splits;
   const int pg0 = split * pps;
   const int pg1 = min(n_pages, pg0 + pps);
-  const bool has_res = (split == P.num_splits - 1) && r > 0;
+  // residual slice of this split: rs tokens per split, handed out from the last split back
+  const int rs = 16 * ((((r + 15) >> 4) + P.num_splits - 1) / P.num_splits);
+  const int t_lo = min(r, (P.num_splits - 1 - split) * rs);
+  const int rcount = min(r, t_lo + rs) - t_lo;
+  const bool has_res = rcount > 0;
   const bool any_work = (pg0 < pg1) || has_res;
 
-  // Start the memory chain first (block table -> first page), then rotate the queries
-  // while those loads are in flight.
+  // ---- start the memory chains first: block table -> first page, and the first pass of
+  // the residual slice; the query rotation below runs while these are in flight ----
+  KeyRegs<BITS, NGK> kr;
+  ValRegs<BITS, NGV> vr;
+  // Block-table entries of this wave's pages (pg0 + wave + 4*it) live in a register, one
+  // per lane, 64 iterations at a time: the page loop itself issues no dependent lookups.
+  const int32_t* table = P.c.block_table + (size_t)b * P.c.max_pages_per_seq;
+  const int pg_first = pg0 + wave;
+  auto load_table = [&](int it0) -> int {
+    const int idx = pg_first + 4 * (it0 + lane);
+    return idx < pg1 ? table[idx] : 0;
+  };
+  int tab = load_table(0);
+  const size_t rb = ((size_t)b * Hkv + kvh) * R;
+  const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
+  const int rtok = tid >> 4;
+  uint4 rk_first = make_uint4(0u, 0u, 0u, 0u);
+  float rn_first = 0.0f;
+  Raw2 rv_first[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) rv_first[j] = Raw2{0u, 0u};
+  if (has_res) {
+    if (rtok < rcount) {
+      rk_first = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + rtok) * D + 8 * n);
+      rn_first = load_meta(P.c.res_norm, rb + t_lo + rtok, P.g.meta_bytes);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = min(4 * j + wave, rcount - 1);
+      rv_first[j] = load_raw2(P.c.res_v, (rb + t_lo + t) * D + 2 * lane, P.c.cfg.io_dtype);
+    }
+  }
+  if (pg_first < pg1) {
+    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
+    kr.load(P, pgi, lane);
+    vr.load(P, pgi, lane);
+  }
 
   // zero the operand tables (rows of absent heads stay zero)
   for (int i = tid; i < 4 * 16 * TABW / 2; i += 256) {
@@ -264,58 +324,54 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   }
   __syncthreads();
 
-  // ---- residual tokens (last split): plain-ALU attention over fp16 K_u and raw V, done
-  // up front so its load latencies overlap the first page fetch; result parked in LDS ----
-  const int tok = tid >> 1, half = tid & 1;  // logits: (token, channel half)
-  const int ch = tid >> 1, th = tid & 1;     // values: (channel, token half)
+  // ---- residual tokens: plain-ALU attention over fp16 K_u and raw V.  The window is cut
+  // into slices (multiples of 16 tokens) dealt to the splits from the last one backwards,
+  // so no workgroup carries the whole window.  Done up front (its loads were issued before
+  // the query rotation); result parked in LDS for the final merge. ----
   if (tid < OSCAR_MAX_GQA) {
     s_wm[4][tid] = -INFINITY;
     s_wl[4][tid] = 0.0f;
   }
   if (has_res) {
-    const int mb = P.g.meta_bytes;
-    const size_t rb = ((size_t)b * Hkv + kvh) * R;
-    const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
-    if (tid < R) s_norm[tid] = tid < r ? load_meta(P.c.res_norm, rb + tid, mb) : 0.0f;
-    __syncthreads();
-    {
-      float acc[OSCAR_MAX_GQA];
-#pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) acc[h] = 0.0f;
-      if (tok < r) {
-        const uint4* kp = reinterpret_cast<const uint4*>(rk + (size_t)tok * D + half * 64);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          float kv[8];
-          halves_to_f32(kp[i], kv);
-          const int j = half * 64 + i * 8;
-#pragma unroll
-          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-            if (h < gq) {
-              const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
-              const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
-              acc[h] = fmaf(qa.x, kv[0], acc[h]);
-              acc[h] = fmaf(qa.y, kv[1], acc[h]);
-              acc[h] = fmaf(qa.z, kv[2], acc[h]);
-              acc[h] = fmaf(qa.w, kv[3], acc[h]);
-              acc[h] = fmaf(qb.x, kv[4], acc[h]);
-              acc[h] = fmaf(qb.y, kv[5], acc[h]);
-              acc[h] = fmaf(qb.z, kv[6], acc[h]);
-              acc[h] = fmaf(qb.w, kv[7], acc[h]);
-            }
-          }
+    // logits: thread (token tid/16 of a 16-token pass, channels 8*(tid%16)..+7)
+    for (int p0 = 0; p0 < rcount; p0 += 16) {
+      uint4 kk = rk_first;
+      float nrm = rn_first;
+      const int t = p0 + rtok;
+      if (p0 > 0) {
+        kk = make_uint4(0u, 0u, 0u, 0u);
+        nrm = 0.0f;
+        if (t < rcount) {
+          kk = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * n);
+          nrm = load_meta(P.c.res_norm, rb + t_lo + t, P.g.meta_bytes);
         }
       }
-      const float nrm = s_norm[tok];
+      float kv[8];
+      halves_to_f32(kk, kv);
 #pragma unroll
       for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-        const float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
-        if (half == 0 && h < gq) s_S[h][tok] = tok < r ? nrm * tot : -INFINITY;
+        if (h < gq) {
+          const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][8 * n]);
+          const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][8 * n + 4]);
+          float acc = qa.x * kv[0];
+          acc = fmaf(qa.y, kv[1], acc);
+          acc = fmaf(qa.z, kv[2], acc);
+          acc = fmaf(qa.w, kv[3], acc);
+          acc = fmaf(qb.x, kv[4], acc);
+          acc = fmaf(qb.y, kv[5], acc);
+          acc = fmaf(qb.z, kv[6], acc);
+          acc = fmaf(qb.w, kv[7], acc);
+          acc = row16_sum(acc);
+          if (n == h) s_S[h][t] = t < rcount ? nrm * acc : -INFINITY;
+        }
       }
     }
     __syncthreads();
+    // softmax statistics of the slice: wave w takes heads w and w+4
+    const int rpad = (rcount + 15) & ~15;
     for (int h = wave; h < gq; h += 4) {
-      const float s0 = s_S[h][lane], s1 = s_S[h][lane + 64];
+      const float s0 = lane < rpad ? s_S[h][lane] : -INFINITY;
+      const float s1 = lane + 64 < rpad ? s_S[h][lane + 64] : -INFINITY;
       const float m_new = wave_max(fmaxf(s0, s1));
       const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
       const float sum = wave_sum(p0 + p1);
@@ -327,30 +383,46 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       }
     }
     __syncthreads();
+    // values: thread (channels 2*lane, 2*lane+1; tokens wave + 4j), four loads in flight
     {
-      float o_res[OSCAR_MAX_GQA];
+      float o0[OSCAR_MAX_GQA], o1[OSCAR_MAX_GQA];
 #pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) o_res[h] = 0.0f;
-      const int t_end = min(r, th * 64 + 64);
-      // 16 independent loads in flight per batch (positions past the end carry p = 0)
-      for (int t0 = th * 64; t0 < t_end; t0 += 16) {
-        float wv[16];
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h) o0[h] = o1[h] = 0.0f;
+      for (int j0 = 0; 4 * j0 + wave < rcount; j0 += 4) {
+        Raw2 rv[4];
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          wv[i] = (t0 + i < t_end) ? load_io(P.c.res_v, (rb + t0 + i) * D + ch, P.c.cfg.io_dtype) : 0.0f;
+        for (int j = 0; j < 4; ++j) {
+          if (j0 == 0) {
+            rv[j] = rv_first[j];
+          } else {
+            const int t = min(4 * (j0 + j) + wave, rcount - 1);
+            rv[j] = load_raw2(P.c.res_v, (rb + t_lo + t) * D + 2 * lane, P.c.cfg.io_dtype);
+          }
+        }
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
+        for (int j = 0; j < 4; ++j) {
+          const int t = 4 * (j0 + j) + wave;   // s_S holds p = 0 for t in [rcount, rpad)
+          const float2 v = raw2_to_f32(rv[j], P.c.cfg.io_dtype);
 #pragma unroll
-          for (int h = 0; h < OSCAR_MAX_GQA; ++h)
-            if (h < gq) o_res[h] = fmaf(s_S[h][t0 + i], wv[i], o_res[h]);
+          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+            if (h < gq) {
+              const float pw = t < rpad ? s_S[h][t] : 0.0f;
+              o0[h] = fmaf(pw, v.x, o0[h]);
+              o1[h] = fmaf(pw, v.y, o1[h]);
+            }
+          }
+        }
       }
-      // both token halves of a channel sit in neighbouring lanes
 #pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-        const float tot = o_res[h] + __shfl_xor(o_res[h], 1, 64);
-        if (th == 0 && h < gq) s_ores[h][ch] = tot;
-      }
+      for (int h = 0; h < OSCAR_MAX_GQA; ++h)
+        if (h < gq) *reinterpret_cast<float2*>(&s_o[wave][h][2 * lane]) = make_float2(o0[h], o1[h]);
     }
+    __syncthreads();
+    for (int i = tid; i < gq * D; i += 256) {
+      const int h = i >> 7, c = i & (D - 1);
+      s_ores[h][c] = (s_o[0][h][c] + s_o[1][h][c]) + (s_o[2][h][c] + s_o[3][h][c]);
+    }
+    __syncthreads();   // s_o is reused by the waves' final hand-off
   }
 
   // ---- per-lane constants ----
@@ -399,22 +471,6 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   _Float16(*A_tab)[TABW] = s_A[wave];
   _Float16(*P_tab)[TABW] = s_P[wave];
 
-  KeyRegs<BITS, NGK> kr;
-  ValRegs<BITS, NGV> vr;
-  // Block-table entries of this wave's pages (pg0 + wave + 4*it) live in a register, one
-  // per lane, 64 iterations at a time: the page loop itself issues no dependent lookups.
-  const int32_t* table = P.c.block_table + (size_t)b * P.c.max_pages_per_seq;
-  const int pg_first = pg0 + wave;
-  auto load_table = [&](int it0) -> int {
-    const int idx = pg_first + 4 * (it0 + lane);
-    return idx < pg1 ? table[idx] : 0;
-  };
-  int tab = load_table(0);
-  if (pg_first < pg1) {
-    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
-    kr.load(P, pgi, lane);
-    vr.load(P, pgi, lane);
-  }
   // Iterations come in chunks of 64 so that the table register is only reloaded between
   // chunks; tabn (lane 0) is the first entry of the following chunk.
   for (int it0 = 0; pg_first + 4 * it0 < pg1; it0 += 64) {
@@ -618,6 +674,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 
   // ---- merge the 4 wave states and the residual state, write the split's record ----
   __syncthreads();
+  const int ch = tid >> 1, th = tid & 1;   // (channel, head parity)
 #pragma unroll
   for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
     if (h < gq && (h & 1) == th) {
@@ -654,12 +711,13 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 }
 
 template <int BITS, int HP>
-int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
+int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipEvent_t e0,
+                  hipEvent_t e1) {
   const int ngk = P.g.ngk, ngv = P.g.ngv;
 #define OSCAR_MFMA_CASE(NK, NV)                                                          \
   if (ngk == NK && ngv == NV) {                                                          \
-    hipLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV>), grid, dim3(256), 0, \
-                       st, P, gq);                                                       \
+    hipExtLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV>), grid, dim3(256), \
+                          0, st, e0, e1, 0, P, gq);                                      \
     return OSCAR_OK;                                                                     \
   }
   OSCAR_MFMA_CASE(1, 4)
@@ -674,14 +732,15 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st) {
 // Launches the matrix-core partial pass when the configuration is one it is built for
 // (fp16 metadata; group sizes (128,32), (32,32) or (128,128)); OSCAR_ERR_UNSUPPORTED
 // tells the caller to use the generic kernel.
-int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st) {
+int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
+                             hipEvent_t e0, hipEvent_t e1) {
   const DecodeParams& P = *reinterpret_cast<const DecodeParams*>(params);
   if (P.c.cfg.meta_dtype != OSCAR_F16) return OSCAR_ERR_UNSUPPORTED;
   const char* force = getenv("OSCAR_DECODE_PATH");
   if (force && force[0] == 'g') return OSCAR_ERR_UNSUPPORTED;  // "generic"
   if (P.g.bits == 2)
-    return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st) : launch_groups<2, 2>(P, gq, grid, st);
+    return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st, e0, e1) : launch_groups<2, 2>(P, gq, grid, st, e0, e1);
   if (P.g.bits == 4)
-    return gq <= 4 ? launch_groups<4, 1>(P, gq, grid, st) : launch_groups<4, 2>(P, gq, grid, st);
+    return gq <= 4 ? launch_groups<4, 1>(P, gq, grid, st, e0, e1) : launch_groups<4, 2>(P, gq, grid, st, e0, e1);
   return OSCAR_ERR_UNSUPPORTED;
 }

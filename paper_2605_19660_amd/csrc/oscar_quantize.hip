@@ -460,13 +460,15 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   }
   } while (false);
 
-  // ---- length update, folded in: the last workgroup to finish (every other one has read
-  // seq_lens / res_lens by then) advances the lengths of all sequences ----
+  // ---- length update, folded in: the last workgroup to finish advances the lengths of all
+  // sequences.  Every other workgroup consumed its loads of seq_lens / res_lens before it
+  // took its ticket, so no fence is needed (an agent-scope fence per workgroup costs a
+  // cache write-back each and nearly doubled the prefill time); the new lengths become
+  // visible to later kernels at the end of this one. ----
   if (P.c.tickets) {
     __shared__ int s_last;
     __syncthreads();
     if (tid == 0) {
-      __threadfence();
       const int total = (int)(gridDim.x * gridDim.y * gridDim.z);
       s_last = (atomicAdd(&P.c.tickets[0], 1) == total - 1) ? 1 : 0;
     }

@@ -27,6 +27,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# each scaled by the same counter's reading for a plain 256 MiB copy kernel (summary under
+# profiles/); counters cannot be read from inside this process, so the figure is keyed by
+# the workload it was measured on and reported as null for any other.
+MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 181_313_126 + 1_114_931}
 LLC_BYTES = 256 << 20       # Infinity Cache
 
 
@@ -208,7 +213,8 @@ def main():
                    "splits": splits, "cache_copies_rotated": n_copies},
         "roofline": {"bound": "hbm", "kernel": "oscar_decode_mfma_kernel (split-K partial pass)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get((w.name, w.bits, splits)),
                      "algorithmic_bytes_per_launch": cache_bytes,
                      "avg_kernel_us": k_us},
         "decode_tokens_per_s": w.batch / (us_step * 1e-6),

@@ -22,8 +22,9 @@
 //
 // Work decomposition: grid (split, kv head, sequence); 4 waves per workgroup, every wave
 // owns whole pages (no barriers in the page loop) and keeps its own online-softmax state;
-// the 4 wave states and the 16-bit residual tokens (handled by the workgroup of the last
-// split with plain ALU code) are merged through LDS at the end.
+// the 4 wave states and the workgroup's slice of the 16-bit residual tokens (plain ALU code,
+// the window is dealt to the splits in multiples of 16 tokens) are merged through LDS at
+// the end.
 // Tile roles: q K^T uses M = query-head limb rows, N = 16 tokens, K = 128 channels;
 // P V uses M = query-head limb rows, N = 16 channels, K = 128 tokens.  A lane of the logit
 // tile is (token n, head group q4), which is also the lane that owns the 8-token operand

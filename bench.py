@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations")
     ap.add_argument("--bits", type=int, default=0, help="override bits (2|4)")
     ap.add_argument("--splits", type=int, default=0, help="override the split-K factor")
+    ap.add_argument("--context", type=int, default=0, help="override the context length (multiple of 128)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch size")
     ap.add_argument("--copies", type=int, default=0, help="override the number of cache copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
@@ -101,6 +103,9 @@ def main():
     w = synth.CONFIGS[args.workload]
     if args.bits:
         w = w.replace(bits=args.bits)
+    if args.context or args.batch:
+        w = w.replace(context=args.context or w.context, batch=args.batch or w.batch,
+                      name="%s-b%d-s%d" % (w.name, args.batch or w.batch, args.context or w.context))
     io = {"f32": ob.F32, "bf16": ob.BF16, "f16": ob.F16}[w.io_dtype]
     meta = {"f32": ob.F32, "f16": ob.F16}[w.meta_dtype]
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,

@@ -96,6 +96,30 @@ __device__ __forceinline__ void split_hi_lo(const float (&x)[8], uint4& hi, uint
   lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
+// fp16 hi + lo limbs of the exact products x0*y.lo, x1*y.hi (y = two packed fp16 values):
+// hi = f16(x*y), lo = f16(fma(x, y, -hi)), each a single mixed-precision FMA that reads its
+// fp16 sources in place and writes one half of the destination register, so neither the
+// multiplier nor the limbs are ever widened, subtracted or packed separately.
+// hi + lo equals the product to ~2^-22.
+__device__ __forceinline__ void mix_split_pair(float x0, float x1, uint32_t y, uint32_t& h,
+                                               uint32_t& l) {
+  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(h) : "v"(x0), "v"(y));
+  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
+      : "+v"(h)
+      : "v"(x1), "v"(y));
+  asm("v_fma_mixlo_f16 %0, %1, %2, -%3 op_sel_hi:[0,1,1]" : "=v"(l) : "v"(x0), "v"(y), "v"(h));
+  asm("v_fma_mixhi_f16 %0, %1, %2, -%3 op_sel:[0,1,1] op_sel_hi:[0,1,1]"
+      : "+v"(l)
+      : "v"(x1), "v"(y), "v"(h));
+}
+__device__ __forceinline__ void mul_split_hi_lo(const float (&x)[8], const uint4& y, uint4& hi,
+                                                uint4& lo) {
+  mix_split_pair(x[0], x[1], y.x, hi.x, lo.x);
+  mix_split_pair(x[2], x[3], y.y, hi.y, lo.y);
+  mix_split_pair(x[4], x[5], y.z, hi.z, lo.z);
+  mix_split_pair(x[6], x[7], y.w, hi.w, lo.w);
+}
+
 // One 32-code chunk -> the four B-operand vectors (k-steps 0..3) of a 16x16x32 MFMA.
 template <int BITS> struct Chunk;
 template <> struct Chunk<2> {
@@ -122,11 +146,26 @@ template <> struct Chunk<4> {
   }
 };
 
+// Page loads go through raw buffer resources (one per pool and page, built on the scalar
+// unit from the wave-uniform page index): the per-lane offset is a loop constant, and a
+// resource of zero length turns the prefetch past a wave's last page into loads that
+// return zeros without touching memory -- the prefetch needs no branch, so the loaded
+// registers are plain loop-carried values (a conditional load made the compiler copy the
+// whole register set, and wait for it, at the end of every iteration).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const void* pool, size_t pgi, int bytes,
+                                                            bool valid) {
+  uint8_t* base = const_cast<uint8_t*>(static_cast<const uint8_t*>(pool)) + pgi * (size_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(base, 0, valid ? bytes : 0, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, int off) {
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+
 // A lane's two chunks of a tile pair: 16 bytes (2-bit) or 32 bytes (4-bit).
 template <int BITS> struct TilePair;
 template <> struct TilePair<2> {
   uint4 v;
-  __device__ __forceinline__ void load(const uint8_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off) { v = buf_load16(r, off); }
   __device__ __forceinline__ Chunk<2> chunk(int i) const {
     Chunk<2> c;
     c.w[0] = i ? v.z : v.x;
@@ -136,9 +175,9 @@ template <> struct TilePair<2> {
 };
 template <> struct TilePair<4> {
   uint4 v[2];
-  __device__ __forceinline__ void load(const uint8_t* p) {
-    v[0] = reinterpret_cast<const uint4*>(p)[0];
-    v[1] = reinterpret_cast<const uint4*>(p)[1];
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off) {
+    v[0] = buf_load16(r, off);
+    v[1] = buf_load16(r, off + 16);
   }
   __device__ __forceinline__ Chunk<4> chunk(int i) const {
     Chunk<4> c;
@@ -154,61 +193,82 @@ template <int BITS, int NGK> struct KeyRegs {
   TilePair<BITS> kc[4];
   uint4 kd[NGK], kz[NGK];  // key Delta / zero of positions 8n..8n+7 (operand order)
   uint4 nr;                // norms of tokens 16*T+n, T = 0..7
-  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane) {
+  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane, bool valid) {
     const int n = lane & 15, q4 = lane >> 4;
-    const uint8_t* kcodes = reinterpret_cast<const uint8_t*>(P.c.k_codes) + pgi * P.g.k_codes_bytes;
-    const uint8_t* kmeta = reinterpret_cast<const uint8_t*>(P.c.k_meta) + pgi * P.g.k_meta_bytes;
-    const uint8_t* knorm = reinterpret_cast<const uint8_t*>(P.c.k_norms) + pgi * P.g.k_norms_bytes;
+    const __amdgpu_buffer_rsrc_t kcodes = page_rsrc(P.c.k_codes, pgi, P.g.k_codes_bytes, valid);
+    const __amdgpu_buffer_rsrc_t kmeta = page_rsrc(P.c.k_meta, pgi, P.g.k_meta_bytes, valid);
+    const __amdgpu_buffer_rsrc_t knorm = page_rsrc(P.c.k_norms, pgi, P.g.k_norms_bytes, valid);
     constexpr int PB = 2 * chunk_bytes(BITS);  // bytes of a lane's tile pair
 #pragma unroll
-    for (int tp = 0; tp < 4; ++tp) kc[tp].load(kcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
+    for (int tp = 0; tp < 4; ++tp) kc[tp].load(kcodes, (tp * 64 + n * 4 + q4) * PB);
 #pragma unroll
     for (int g = 0; g < NGK; ++g) {
-      kd[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)(g * D + 8 * n) * 2);
-      kz[g] = *reinterpret_cast<const uint4*>(kmeta + (size_t)((NGK + g) * D + 8 * n) * 2);
+      kd[g] = buf_load16(kmeta, (g * D + 8 * n) * 2);
+      kz[g] = buf_load16(kmeta, ((NGK + g) * D + 8 * n) * 2);
     }
-    nr = *reinterpret_cast<const uint4*>(knorm + (size_t)(8 * n) * 2);
+    nr = buf_load16(knorm, 8 * n * 2);
   }
 };
 template <int BITS, int NGV> struct ValRegs {
   TilePair<BITS> vc[4];
   uint4 vd[NGV], vz[NGV];  // value Delta / zero of tokens 16*T+n
-  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane) {
+  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane, bool valid) {
     const int n = lane & 15, q4 = lane >> 4;
-    const uint8_t* vcodes = reinterpret_cast<const uint8_t*>(P.c.v_codes) + pgi * P.g.v_codes_bytes;
-    const uint8_t* vmeta = reinterpret_cast<const uint8_t*>(P.c.v_meta) + pgi * P.g.v_meta_bytes;
+    const __amdgpu_buffer_rsrc_t vcodes = page_rsrc(P.c.v_codes, pgi, P.g.v_codes_bytes, valid);
+    const __amdgpu_buffer_rsrc_t vmeta = page_rsrc(P.c.v_meta, pgi, P.g.v_meta_bytes, valid);
     constexpr int PB = 2 * chunk_bytes(BITS);
 #pragma unroll
-    for (int tp = 0; tp < 4; ++tp) vc[tp].load(vcodes + (size_t)(tp * 64 + n * 4 + q4) * PB);
+    for (int tp = 0; tp < 4; ++tp) vc[tp].load(vcodes, (tp * 64 + n * 4 + q4) * PB);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
-      vd[g] = *reinterpret_cast<const uint4*>(vmeta + (size_t)(g * R + 8 * n) * 2);
-      vz[g] = *reinterpret_cast<const uint4*>(vmeta + (size_t)((NGV + g) * R + 8 * n) * 2);
+      vd[g] = buf_load16(vmeta, (g * R + 8 * n) * 2);
+      vz[g] = buf_load16(vmeta, ((NGV + g) * R + 8 * n) * 2);
     }
   }
 };
 
-// two neighbouring values of the caller's dtype, held raw until they are needed
-struct Raw2 {
-  uint32_t a, b;
-};
-__device__ __forceinline__ Raw2 load_raw2(const void* p, size_t idx, int dt) {
-  Raw2 r;
-  if (dt == OSCAR_F32) {
-    const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const float*>(p) + idx);
-    r.a = v.x;
-    r.b = v.y;
-  } else {
-    r.a = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(p) + idx);
-    r.b = 0u;
+// One residual token's share for a lane: 8 channels of K_u (fp16), of V (caller's dtype),
+// and the token norm, held raw until the query rotation is done.
+struct ResTok {
+  uint4 k, v0, v1;
+  uint32_t nrm;
+  __device__ __forceinline__ void load(const DecodeParams& P, const __half* rk, size_t rb, int t_lo,
+                                       int t, int rcount, int n) {
+    k = v0 = v1 = make_uint4(0u, 0u, 0u, 0u);
+    nrm = 0u;
+    if (t < rcount) {
+      const size_t tok = rb + t_lo + t;
+      k = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * n);
+      if (P.c.cfg.io_dtype == OSCAR_F32) {
+        const uint4* vp = reinterpret_cast<const uint4*>(static_cast<const float*>(P.c.res_v) + tok * D + 8 * n);
+        v0 = vp[0];
+        v1 = vp[1];
+      } else {
+        v0 = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(P.c.res_v) + tok * D + 8 * n);
+      }
+      if (P.g.meta_bytes == 4) nrm = static_cast<const uint32_t*>(P.c.res_norm)[tok];
+      else nrm = static_cast<const uint16_t*>(P.c.res_norm)[tok];
+    }
   }
-  return r;
-}
-__device__ __forceinline__ float2 raw2_to_f32(const Raw2& r, int dt) {
-  if (dt == OSCAR_F32) return make_float2(__uint_as_float(r.a), __uint_as_float(r.b));
-  if (dt == OSCAR_BF16) return make_float2(__uint_as_float(r.a << 16), __uint_as_float(r.a & 0xffff0000u));
-  return make_float2(__half2float(__ushort_as_half((unsigned short)(r.a & 0xffffu))),
-                     __half2float(__ushort_as_half((unsigned short)(r.a >> 16))));
+  __device__ __forceinline__ void values(float (&x)[8], int dt) const {
+    if (dt == OSCAR_F32) {
+      x[0] = __uint_as_float(v0.x); x[1] = __uint_as_float(v0.y);
+      x[2] = __uint_as_float(v0.z); x[3] = __uint_as_float(v0.w);
+      x[4] = __uint_as_float(v1.x); x[5] = __uint_as_float(v1.y);
+      x[6] = __uint_as_float(v1.z); x[7] = __uint_as_float(v1.w);
+    } else if (dt == OSCAR_BF16) {
+      x[0] = __uint_as_float(v0.x << 16); x[1] = __uint_as_float(v0.x & 0xffff0000u);
+      x[2] = __uint_as_float(v0.y << 16); x[3] = __uint_as_float(v0.y & 0xffff0000u);
+      x[4] = __uint_as_float(v0.z << 16); x[5] = __uint_as_float(v0.z & 0xffff0000u);
+      x[6] = __uint_as_float(v0.w << 16); x[7] = __uint_as_float(v0.w & 0xffff0000u);
+    } else {
+      halves_to_f32(v0, x);
+    }
+  }
+};
+__device__ __forceinline__ float load_meta_bits(uint32_t bits, int meta_bytes) {
+  if (meta_bytes == 4) return __uint_as_float(bits);
+  return __half2float(__ushort_as_half((unsigned short)bits));
 }
 
 __device__ __forceinline__ float max8_halves(const uint4& r) {
@@ -236,10 +296,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   __shared__ __align__(16) _Float16 s_A[4][16][TABW];   // per wave: (Q_h Delta_k) hi/lo rows
   __shared__ __align__(16) _Float16 s_P[4][16][TABW];   // per wave: (p Delta_v) hi/lo rows
   __shared__ __align__(16) float s_o[4][OSCAR_MAX_GQA][D];  // wave results for the merge
-  __shared__ __align__(16) float s_ores[OSCAR_MAX_GQA][D];  // residual-window result
-  __shared__ float s_wm[5][OSCAR_MAX_GQA], s_wl[5][OSCAR_MAX_GQA];
-  // residual phase
-  __shared__ __align__(16) float s_S[OSCAR_MAX_GQA][R];
+  __shared__ float s_wm[4][OSCAR_MAX_GQA], s_wl[4][OSCAR_MAX_GQA];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -248,109 +305,118 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   const int n = lane & 15, q4 = lane >> 4;
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
 
+  // Pages are dealt round-robin: wave w of split s owns pages 4*s + w + 4*S*k.  The page
+  // numbers (and so the block-table addresses) do not depend on the sequence length, which
+  // lets the length, table, query and residual loads all start together.
+  const int pstride = 4 * P.num_splits;
+  const int pg_first = 4 * split + wave;
+  const int32_t* table = P.c.block_table + (size_t)b * P.c.max_pages_per_seq;
+  // Block-table entries of this wave's pages live in a register, one per lane, 64
+  // iterations at a time: the page loop itself issues no dependent lookups.  Entries past
+  // the sequence's last page are never used for an access.
+  auto load_table = [&](int it0) -> int {
+    const int idx = pg_first + pstride * (it0 + lane);
+    return idx < P.c.max_pages_per_seq ? table[idx] : 0;
+  };
+  int tab = load_table(0);
+  // queries of the heads this wave rotates (w and w+4): channels (lane, lane+64)
+  float qx[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int h = min(wave + 4 * i, gq - 1);
+    const size_t qb = ((size_t)b * Hq + (size_t)kvh * gq + h) * D;
+    qx[i][0] = load_io(P.q, qb + lane, P.c.cfg.io_dtype);
+    qx[i][1] = load_io(P.q, qb + lane + 64, P.c.cfg.io_dtype);
+  }
+
   const int seq_len = P.c.seq_lens[b];
   const int r = P.c.res_lens[b];
   const int n_pages = (seq_len - r) / R;
-  const int pps = (n_pages + P.num_splits - 1) / P.num_splits;
-  const int pg0 = split * pps;
-  const int pg1 = min(n_pages, pg0 + pps);
-  // residual slice of this split: rs tokens per split, handed out from the last split back
+  // Residual slice of this split: rs tokens per split (a multiple of 16), handed out from
+  // the last split backwards; inside the workgroup, wave w takes tokens 16*pass + 4*w + j.
   const int rs = 16 * ((((r + 15) >> 4) + P.num_splits - 1) / P.num_splits);
   const int t_lo = min(r, (P.num_splits - 1 - split) * rs);
   const int rcount = min(r, t_lo + rs) - t_lo;
-  const bool has_res = rcount > 0;
-  const bool any_work = (pg0 < pg1) || has_res;
+  const bool wave_res = 4 * wave < rcount;
 
-  // ---- start the memory chains first: block table -> first page, and the first pass of
-  // the residual slice; the query rotation below runs while these are in flight ----
+  // ---- first page and first residual pass: issued before anything is computed ----
   KeyRegs<BITS, NGK> kr;
   ValRegs<BITS, NGV> vr;
-  // Block-table entries of this wave's pages (pg0 + wave + 4*it) live in a register, one
-  // per lane, 64 iterations at a time: the page loop itself issues no dependent lookups.
-  const int32_t* table = P.c.block_table + (size_t)b * P.c.max_pages_per_seq;
-  const int pg_first = pg0 + wave;
-  auto load_table = [&](int it0) -> int {
-    const int idx = pg_first + 4 * (it0 + lane);
-    return idx < pg1 ? table[idx] : 0;
-  };
-  int tab = load_table(0);
+  {
+    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
+    kr.load(P, pgi, lane, pg_first < n_pages);
+    vr.load(P, pgi, lane, pg_first < n_pages);
+  }
   const size_t rb = ((size_t)b * Hkv + kvh) * R;
   const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
-  const int rtok = tid >> 4;
-  uint4 rk_first = make_uint4(0u, 0u, 0u, 0u);
-  float rn_first = 0.0f;
-  Raw2 rv_first[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) rv_first[j] = Raw2{0u, 0u};
-  if (has_res) {
-    if (rtok < rcount) {
-      rk_first = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + rtok) * D + 8 * n);
-      rn_first = load_meta(P.c.res_norm, rb + t_lo + rtok, P.g.meta_bytes);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int t = min(4 * j + wave, rcount - 1);
-      rv_first[j] = load_raw2(P.c.res_v, (rb + t_lo + t) * D + 2 * lane, P.c.cfg.io_dtype);
-    }
-  }
-  if (pg_first < pg1) {
-    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
-    kr.load(P, pgi, lane);
-    vr.load(P, pgi, lane);
-  }
+  ResTok rt_first;
+  rt_first.load(P, rk, rb, t_lo, 4 * wave + q4, rcount, n);
 
   // zero the operand tables (rows of absent heads stay zero)
-  for (int i = tid; i < 4 * 16 * TABW / 2; i += 256) {
-    reinterpret_cast<uint32_t*>(&s_A[0][0][0])[i] = 0u;
-    reinterpret_cast<uint32_t*>(&s_P[0][0][0])[i] = 0u;
+  for (int i = tid; i < 4 * 16 * TABW / 8; i += 256) {
+    reinterpret_cast<uint4*>(&s_A[0][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
+    reinterpret_cast<uint4*>(&s_P[0][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
   }
   // Q_h = H(q)/sqrt(128) * scale*log2(e): wave w rotates heads w and w+4 on its own; a lane
   // holds channels (lane, lane+64): stage 64 in registers, stages 1..32 across lanes.
-  if (any_work) {
-    for (int h = wave; h < gq; h += 4) {
-      const size_t qb = ((size_t)b * Hq + (size_t)kvh * gq + h) * D;
-      float x0 = load_io(P.q, qb + lane, P.c.cfg.io_dtype);
-      float x1 = load_io(P.q, qb + lane + 64, P.c.cfg.io_dtype);
 #pragma unroll
-      for (int m = 1; m < 64; m <<= 1) {
-        const float y0 = __shfl_xor(x0, m, 64), y1 = __shfl_xor(x1, m, 64);
-        const bool up = (lane & m) != 0;
-        x0 = up ? y0 - x0 : x0 + y0;
-        x1 = up ? y1 - x1 : x1 + y1;
-      }
-      const float c = 0.08838834764831845f * P.qk_scale_log2;
+  for (int i = 0; i < 2; ++i) {
+    const int h = wave + 4 * i;
+    float x0 = qx[i][0], x1 = qx[i][1];
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+      const float y0 = __shfl_xor(x0, m, 64), y1 = __shfl_xor(x1, m, 64);
+      const bool up = (lane & m) != 0;
+      x0 = up ? y0 - x0 : x0 + y0;
+      x1 = up ? y1 - x1 : x1 + y1;
+    }
+    const float c = 0.08838834764831845f * P.qk_scale_log2;
+    if (h < gq) {
       s_q[h][lane] = (x0 + x1) * c;
       s_q[h][lane + 64] = (x0 - x1) * c;
     }
   }
   __syncthreads();
 
-  // ---- residual tokens: plain-ALU attention over fp16 K_u and raw V.  The window is cut
-  // into slices (multiples of 16 tokens) dealt to the splits from the last one backwards,
-  // so no workgroup carries the whole window.  Done up front (its loads were issued before
-  // the query rotation); result parked in LDS for the final merge. ----
-  if (tid < OSCAR_MAX_GQA) {
-    s_wm[4][tid] = -INFINITY;
-    s_wl[4][tid] = 0.0f;
-  }
-  if (has_res) {
-    // logits: thread (token tid/16 of a 16-token pass, channels 8*(tid%16)..+7)
-    for (int p0 = 0; p0 < rcount; p0 += 16) {
-      uint4 kk = rk_first;
-      float nrm = rn_first;
-      const int t = p0 + rtok;
-      if (p0 > 0) {
-        kk = make_uint4(0u, 0u, 0u, 0u);
-        nrm = 0.0f;
-        if (t < rcount) {
-          kk = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * n);
-          nrm = load_meta(P.c.res_norm, rb + t_lo + t, P.g.meta_bytes);
-        }
-      }
-      float kv[8];
-      halves_to_f32(kk, kv);
+  // ---- wave state: online softmax over this wave's pages, seeded by its residual tokens ----
+  float m_run[HP], l_run[HP], bv[HP][NGV];
+  float4v O[8];
 #pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
+  for (int s = 0; s < HP; ++s) {
+    m_run[s] = -INFINITY;
+    l_run[s] = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) bv[s][g] = 0.0f;
+  }
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) O[ct] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
+  // accumulator scale: O holds out * 2^-(24 - xv_cur - offset); this start value makes it 1
+  int xv_cur = 24 - slot_bitpos_min(BITS);
+
+  // ---- residual tokens: plain-ALU attention over fp16 K_u and raw V, wave-local.  A lane
+  // is (token j = lane/16 of the wave's four, channels 8n..8n+7); logits are reduced over
+  // the 16 lanes of a row, the softmax state over the four rows.  The result becomes the
+  // starting state of the wave's accumulators, so it costs no workgroup barrier. ----
+  if (wave_res) {
+    constexpr int NH = 4 * HP;
+    float mw[NH], lw[NH], ow[NH][8];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      mw[h] = -INFINITY;
+      lw[h] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) ow[h][c] = 0.0f;
+    }
+    for (int p0 = 0; p0 + 4 * wave < rcount; p0 += 16) {
+      ResTok rt = rt_first;
+      if (p0 > 0) rt.load(P, rk, rb, t_lo, p0 + 4 * wave + q4, rcount, n);
+      const bool valid = p0 + 4 * wave + q4 < rcount;
+      float kv[8], vv[8];
+      halves_to_f32(rt.k, kv);
+      rt.values(vv, P.c.cfg.io_dtype);
+      const float nrm = valid ? load_meta_bits(rt.nrm, P.g.meta_bytes) : 0.0f;
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
         if (h < gq) {
           const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][8 * n]);
           const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][8 * n + 4]);
@@ -362,68 +428,57 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
           acc = fmaf(qb.y, kv[5], acc);
           acc = fmaf(qb.z, kv[6], acc);
           acc = fmaf(qb.w, kv[7], acc);
-          acc = row16_sum(acc);
-          if (n == h) s_S[h][t] = t < rcount ? nrm * acc : -INFINITY;
+          const float sc = valid ? nrm * row16_sum(acc) : -INFINITY;
+          float mx = fmaxf(sc, __shfl_xor(sc, 16, 64));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          // the wave's first token (row 0 of its first pass) is valid, so mx is finite
+          const float m_new = fmaxf(mw[h], mx);
+          const float alpha = __builtin_amdgcn_exp2f(mw[h] - m_new);
+          const float pw = __builtin_amdgcn_exp2f(sc - m_new);
+          mw[h] = m_new;
+          lw[h] = lw[h] * alpha + pw;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) ow[h][c] = fmaf(pw, vv[c], ow[h][c] * alpha);
         }
       }
     }
-    __syncthreads();
-    // softmax statistics of the slice: wave w takes heads w and w+4
-    const int rpad = (rcount + 15) & ~15;
-    for (int h = wave; h < gq; h += 4) {
-      const float s0 = lane < rpad ? s_S[h][lane] : -INFINITY;
-      const float s1 = lane + 64 < rpad ? s_S[h][lane + 64] : -INFINITY;
-      const float m_new = wave_max(fmaxf(s0, s1));
-      const float p0 = __builtin_amdgcn_exp2f(s0 - m_new), p1 = __builtin_amdgcn_exp2f(s1 - m_new);
-      const float sum = wave_sum(p0 + p1);
-      s_S[h][lane] = p0;
-      s_S[h][lane + 64] = p1;
-      if (lane == 0) {
-        s_wm[4][h] = m_new;
-        s_wl[4][h] = sum;
-      }
-    }
-    __syncthreads();
-    // values: thread (channels 2*lane, 2*lane+1; tokens wave + 4j), four loads in flight
-    {
-      float o0[OSCAR_MAX_GQA], o1[OSCAR_MAX_GQA];
+    // sum the four rows, hand the result over in accumulator layout through the wave's
+    // own slice of s_o (written again only by this wave, at the very end)
 #pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h) o0[h] = o1[h] = 0.0f;
-      for (int j0 = 0; 4 * j0 + wave < rcount; j0 += 4) {
-        Raw2 rv[4];
+    for (int h = 0; h < NH; ++h) {
+      if (h < gq) {
+        lw[h] += __shfl_xor(lw[h], 16, 64);
+        lw[h] += __shfl_xor(lw[h], 32, 64);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (j0 == 0) {
-            rv[j] = rv_first[j];
-          } else {
-            const int t = min(4 * (j0 + j) + wave, rcount - 1);
-            rv[j] = load_raw2(P.c.res_v, (rb + t_lo + t) * D + 2 * lane, P.c.cfg.io_dtype);
-          }
+        for (int c = 0; c < 8; ++c) {
+          ow[h][c] += __shfl_xor(ow[h][c], 16, 64);
+          ow[h][c] += __shfl_xor(ow[h][c], 32, 64);
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int t = 4 * (j0 + j) + wave;   // s_S holds p = 0 for t in [rcount, rpad)
-          const float2 v = raw2_to_f32(rv[j], P.c.cfg.io_dtype);
-#pragma unroll
-          for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-            if (h < gq) {
-              const float pw = t < rpad ? s_S[h][t] : 0.0f;
-              o0[h] = fmaf(pw, v.x, o0[h]);
-              o1[h] = fmaf(pw, v.y, o1[h]);
-            }
-          }
+        if (q4 == 0) {
+          *reinterpret_cast<float4*>(&s_o[wave][h][8 * n]) = make_float4(ow[h][0], ow[h][1], ow[h][2], ow[h][3]);
+          *reinterpret_cast<float4*>(&s_o[wave][h][8 * n + 4]) = make_float4(ow[h][4], ow[h][5], ow[h][6], ow[h][7]);
         }
       }
+    }
+    wave_lds_fence();
 #pragma unroll
-      for (int h = 0; h < OSCAR_MAX_GQA; ++h)
-        if (h < gq) *reinterpret_cast<float2*>(&s_o[wave][h][2 * lane]) = make_float2(o0[h], o1[h]);
+    for (int s = 0; s < HP; ++s) {
+      const int h = q4 + 4 * s;
+      if (h < gq) {
+        // (the compiler selects mw[h], lw[h] by q4; NH is at most 8)
+        float mh = mw[0], lh = lw[0];
+#pragma unroll
+        for (int hh = 1; hh < NH; ++hh) {
+          mh = (hh == h) ? mw[hh] : mh;
+          lh = (hh == h) ? lw[hh] : lh;
+        }
+        m_run[s] = mh;
+        l_run[s] = (n == 0) ? lh : 0.0f;   // l_run is summed over the 16 lanes at the end
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) O[ct][2 * s] = s_o[wave][h][16 * ct + n];
+      }
     }
-    __syncthreads();
-    for (int i = tid; i < gq * D; i += 256) {
-      const int h = i >> 7, c = i & (D - 1);
-      s_ores[h][c] = (s_o[0][h][c] + s_o[1][h][c]) + (s_o[2][h][c] + s_o[3][h][c]);
-    }
-    __syncthreads();   // s_o is reused by the waves' final hand-off
+    wave_lds_fence();
   }
 
   // ---- per-lane constants ----
@@ -436,7 +491,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int chan = 32 * (n >> 2) + slot_index(BITS, n & 3, i);
-      qr[s][i] = (h < gq && any_work) ? s_q[h][chan] : 0.0f;
+      qr[s][i] = (h < gq) ? s_q[h][chan] : 0.0f;
       mx = fmaxf(mx, fabsf(qr[s][i]));
     }
     mx = row16_max(mx);
@@ -455,64 +510,46 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   for (int T = 0; T < 8; ++T)
     vsc0[T] = ldexpf(1.0f, slot_bitpos_min(BITS) - slot_bitpos(BITS, n >> 2, T));
 
-  // ---- wave state ----
-  float m_run[HP], l_run[HP], bv[HP][NGV];
-  float4v O[8];
-#pragma unroll
-  for (int s = 0; s < HP; ++s) {
-    m_run[s] = -INFINITY;
-    l_run[s] = 0.0f;
-#pragma unroll
-    for (int g = 0; g < NGV; ++g) bv[s][g] = 0.0f;
-  }
-#pragma unroll
-  for (int ct = 0; ct < 8; ++ct) O[ct] = (float4v){0.0f, 0.0f, 0.0f, 0.0f};
-  int xv_cur = 0;
-
   _Float16(*A_tab)[TABW] = s_A[wave];
   _Float16(*P_tab)[TABW] = s_P[wave];
 
   // Iterations come in chunks of 64 so that the table register is only reloaded between
   // chunks; tabn (lane 0) is the first entry of the following chunk.
-  for (int it0 = 0; pg_first + 4 * it0 < pg1; it0 += 64) {
+  for (int it0 = 0; pg_first + pstride * it0 < n_pages; it0 += 64) {
   if (it0 > 0) tab = load_table(it0);
   const int tabn = load_table(it0 + 64);
-  const int it_end = min(64, (pg1 - pg_first - 4 * it0 + 3) / 4);
+  const int it_end = min(64, (n_pages - pg_first - pstride * it0 + pstride - 1) / pstride);
   // touch both registers here, so the wait for these two loads sits outside the page loop
   // (inside it, it would also wait for every prefetch in flight)
   asm volatile("" ::"v"(tab), "v"(tabn));
   for (int iti = 0; iti < it_end; ++iti) {
-    const int pg = pg_first + 4 * (it0 + iti);
-    const bool has_next = pg + 4 < pg1;
-    size_t next_pgi = 0;
-    if (has_next) {
-      const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
-                                : __builtin_amdgcn_readlane(tabn, 0);
-      next_pgi = (size_t)phys * Hkv + kvh;
-    }
+    const int pg = pg_first + pstride * (it0 + iti);
+    const bool has_next = pg + pstride < n_pages;
+    // entries past the wave's last page read as 0 (a valid page index) and the load is void
+    const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
+                              : __builtin_amdgcn_readlane(tabn, 0);
+    const size_t next_pgi = (size_t)phys * Hkv + kvh;
 
     // ---- q K^T ----
     float S[HP][8];
     {
-      float nt[8];
-      halves_to_f32(kr.nr, nt);
+      const half8 nt = __builtin_bit_cast(half8, kr.nr);
 #pragma unroll
       for (int g = 0; g < NGK; ++g) {
-        float dk[8], zk[8];
-        halves_to_f32(kr.kd[g], dk);
-        halves_to_f32(kr.kz[g], zk);
+        const half8 dk = __builtin_bit_cast(half8, kr.kd[g]);
+        const half8 zk = __builtin_bit_cast(half8, kr.kz[g]);
+        float dz[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dz[i] = (float)dk[i] * (float)zk[i];
         float bias[HP];
 #pragma unroll
         for (int s = 0; s < HP; ++s) {
-          float a[8], bp = 0.0f;
+          float bp = 0.0f;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            a[i] = qs[s][i] * dk[i];
-            bp = fmaf(qr[s][i] * dk[i], zk[i], bp);
-          }
+          for (int i = 0; i < 8; ++i) bp = fmaf(qr[s][i], dz[i], bp);
           bias[s] = row16_sum(bp);
           uint4 hi, lo;
-          split_hi_lo(a, hi, lo);
+          mul_split_hi_lo(qs[s], kr.kd[g], hi, lo);
           const int h = q4 + 4 * s;
           if (h < gq) {
             *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
@@ -542,14 +579,14 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
           }
 #pragma unroll
           for (int s = 0; s < HP; ++s) {
-            S[s][T] = nt[T] * fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]);
-            S[s][T + 1] = nt[T + 1] * fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]);
+            S[s][T] = (float)nt[T] * fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]);
+            S[s][T + 1] = (float)nt[T + 1] * fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]);
           }
         }
       }
     }
     // the key registers are free: fetch the next page's key side behind the value work
-    if (has_next) kr.load(P, next_pgi, lane);
+    kr.load(P, next_pgi, lane, has_next);
 
     // ---- online softmax (per head slot; the 16 lanes of a group share a head) ----
     float alpha[HP];
@@ -603,23 +640,26 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 
     // ---- P V, one value group at a time through the wave's LDS table ----
     const float pscale = ldexpf(1.0f, xv);
+    float pc[HP][8];   // p * 2^(xv - slot offset): the value operand before Delta_v
+#pragma unroll
+    for (int s = 0; s < HP; ++s)
+#pragma unroll
+      for (int T = 0; T < 8; ++T) pc[s][T] = S[s][T] * (vsc0[T] * pscale);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
-      float dv[8], zv[8];
-      halves_to_f32(vr.vd[g], dv);
-      halves_to_f32(vr.vz[g], zv);
+      const half8 dv = __builtin_bit_cast(half8, vr.vd[g]);
+      const half8 zv = __builtin_bit_cast(half8, vr.vz[g]);
+      float dz[8];
+#pragma unroll
+      for (int T = 0; T < 8; ++T) dz[T] = (float)dv[T] * (float)zv[T];
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
-        float a[8], acc_b = 0.0f;
+        float acc_b = 0.0f;
 #pragma unroll
-        for (int T = 0; T < 8; ++T) {
-          const float pd = S[s][T] * dv[T];
-          a[T] = pd * (vsc0[T] * pscale);
-          acc_b = fmaf(pd, zv[T], acc_b);
-        }
+        for (int T = 0; T < 8; ++T) acc_b = fmaf(S[s][T], dz[T], acc_b);
         bv[s][g] += acc_b;
         uint4 hi, lo;
-        split_hi_lo(a, hi, lo);
+        mul_split_hi_lo(pc[s], vr.vd[g], hi, lo);
         const int h = q4 + 4 * s;
         if (h < gq) {
           *reinterpret_cast<uint4*>(&P_tab[row_hi(h)][8 * n]) = hi;
@@ -647,7 +687,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
         }
       }
     }
-    if (has_next) vr.load(P, next_pgi, lane);
+    vr.load(P, next_pgi, lane, has_next);
   }
   }
 
@@ -679,12 +719,11 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 #pragma unroll
   for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
     if (h < gq && (h & 1) == th) {
-      float M = s_wm[4][h];
+      float M = -INFINITY;
 #pragma unroll
       for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
       float acc = 0.0f;
       if (M != -INFINITY) {
-        if (s_wm[4][h] != -INFINITY) acc = s_ores[h][ch] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
           if (s_wm[w][h] != -INFINITY) acc += s_o[w][h][ch] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);
@@ -695,12 +734,11 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   }
   if (tid < gq) {
     const int h = tid;
-    float M = s_wm[4][h];
+    float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
     float L = 0.0f;
     if (M != -INFINITY) {
-      L = s_wl[4][h] * __builtin_amdgcn_exp2f(s_wm[4][h] - M);
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         if (s_wm[w][h] != -INFINITY) L += s_wl[w][h] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);

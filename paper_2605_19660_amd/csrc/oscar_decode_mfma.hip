@@ -96,28 +96,61 @@ __device__ __forceinline__ void split_hi_lo(const float (&x)[8], uint4& hi, uint
   lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
-// fp16 hi + lo limbs of the exact products x0*y.lo, x1*y.hi (y = two packed fp16 values):
+// fp16 hi[8] + lo[8] limbs of the exact products x[i] * y[i] (y = 8 packed fp16 values):
 // hi = f16(x*y), lo = f16(fma(x, y, -hi)), each a single mixed-precision FMA that reads its
 // fp16 sources in place and writes one half of the destination register, so neither the
 // multiplier nor the limbs are ever widened, subtracted or packed separately.
 // hi + lo equals the product to ~2^-22.
-__device__ __forceinline__ void mix_split_pair(float x0, float x1, uint32_t y, uint32_t& h,
-                                               uint32_t& l) {
-  asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(h) : "v"(x0), "v"(y));
-  asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
-      : "+v"(h)
-      : "v"(x1), "v"(y));
-  asm("v_fma_mixlo_f16 %0, %1, %2, -%3 op_sel_hi:[0,1,1]" : "=v"(l) : "v"(x0), "v"(y), "v"(h));
-  asm("v_fma_mixhi_f16 %0, %1, %2, -%3 op_sel:[0,1,1] op_sel_hi:[0,1,1]"
-      : "+v"(l)
-      : "v"(x1), "v"(y), "v"(h));
-}
+// One block of 16 instructions: a half-register write must not be followed directly by a
+// vector instruction that reads the register (the compiler cannot see into the block to
+// insert the wait state itself); here every such read comes four instructions after the
+// write, and the block ends with a wait state of its own.
 __device__ __forceinline__ void mul_split_hi_lo(const float (&x)[8], const uint4& y, uint4& hi,
                                                 uint4& lo) {
-  mix_split_pair(x[0], x[1], y.x, hi.x, lo.x);
-  mix_split_pair(x[2], x[3], y.y, hi.y, lo.y);
-  mix_split_pair(x[4], x[5], y.z, hi.z, lo.z);
-  mix_split_pair(x[6], x[7], y.w, hi.w, lo.w);
+  uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+  asm volatile("v_fma_mixlo_f16 %0, %8, %16, 0 op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixlo_f16 %1, %10, %17, 0 op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixlo_f16 %2, %12, %18, 0 op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixlo_f16 %3, %14, %19, 0 op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixhi_f16 %0, %9, %16, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixhi_f16 %1, %11, %17, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixhi_f16 %2, %13, %18, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixhi_f16 %3, %15, %19, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]\n\t"
+      "v_fma_mixlo_f16 %4, %8, %16, -%0 op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixlo_f16 %5, %10, %17, -%1 op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixlo_f16 %6, %12, %18, -%2 op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixlo_f16 %7, %14, %19, -%3 op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixhi_f16 %4, %9, %16, -%0 op_sel:[0,1,1] op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixhi_f16 %5, %11, %17, -%1 op_sel:[0,1,1] op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixhi_f16 %6, %13, %18, -%2 op_sel:[0,1,1] op_sel_hi:[0,1,1]\n\t"
+      "v_fma_mixhi_f16 %7, %15, %19, -%3 op_sel:[0,1,1] op_sel_hi:[0,1,1]\n\t"
+      "s_nop 0"
+      : "=&v"(h0), "=&v"(h1), "=&v"(h2), "=&v"(h3), "=&v"(l0), "=&v"(l1), "=&v"(l2), "=&v"(l3)
+      : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]),
+        "v"(y.x), "v"(y.y), "v"(y.z), "v"(y.w));
+  hi = make_uint4(h0, h1, h2, h3);
+  lo = make_uint4(l0, l1, l2, l3);
+}
+
+// Products of packed fp16 pairs in fp32, and fp16 * fp32, without widening instructions:
+// the mixed-precision FMA reads fp16 sources in place.  (All of these blocks are volatile:
+// as plain asm the (32,32)-group kernel came out with wrong logits.)
+__device__ __forceinline__ void mix_mul_pair(uint32_t a, uint32_t b, float& lo, float& hi) {
+  asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,1,0]" : "=v"(lo) : "v"(a), "v"(b));
+  asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(hi) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mix_mul8(const uint4& a, const uint4& b, float (&x)[8]) {
+  mix_mul_pair(a.x, b.x, x[0], x[1]);
+  mix_mul_pair(a.y, b.y, x[2], x[3]);
+  mix_mul_pair(a.z, b.z, x[4], x[5]);
+  mix_mul_pair(a.w, b.w, x[6], x[7]);
+}
+// x * (fp16 half `hi_half` of packed h)
+template <int HI> __device__ __forceinline__ float mix_scale(float x, uint32_t h) {
+  float r;
+  if (HI) asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]" : "=v"(r) : "v"(x), "v"(h));
+  else asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(r) : "v"(x), "v"(h));
+  return r;
 }
 
 // One 32-code chunk -> the four B-operand vectors (k-steps 0..3) of a 16x16x32 MFMA.
@@ -271,14 +304,21 @@ __device__ __forceinline__ float load_meta_bits(uint32_t bits, int meta_bytes) {
   return __half2float(__ushort_as_half((unsigned short)bits));
 }
 
+// Step sizes are non-negative fp16 numbers, which order like their bit patterns: packed
+// unsigned 16-bit max needs no NaN canonicalization.
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a),
+                                                                __builtin_bit_cast(ushort2v, b)));
+}
+__device__ __forceinline__ uint4 pk_max4(const uint4& a, const uint4& b) {
+  return make_uint4(pk_max_u16(a.x, b.x), pk_max_u16(a.y, b.y), pk_max_u16(a.z, b.z),
+                    pk_max_u16(a.w, b.w));
+}
 __device__ __forceinline__ float max8_halves(const uint4& r) {
-  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-  h2 a = __builtin_bit_cast(h2, r.x), b = __builtin_bit_cast(h2, r.y);
-  h2 c = __builtin_bit_cast(h2, r.z), d = __builtin_bit_cast(h2, r.w);
-  a = __builtin_elementwise_max(a, b);
-  c = __builtin_elementwise_max(c, d);
-  a = __builtin_elementwise_max(a, c);
-  return fmaxf((float)a[0], (float)a[1]);
+  const uint32_t m = pk_max_u16(pk_max_u16(r.x, r.y), pk_max_u16(r.z, r.w));
+  const uint32_t t = max(m & 0xffffu, m >> 16);
+  return __half2float(__ushort_as_half((unsigned short)t));
 }
 
 // rows of the 16-row operand tile: head h -> hi row 4*(h%4) + 2*(h/4), lo row + 1, so the
@@ -533,14 +573,11 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     // ---- q K^T ----
     float S[HP][8];
     {
-      const half8 nt = __builtin_bit_cast(half8, kr.nr);
+      const uint32_t nt[4] = {kr.nr.x, kr.nr.y, kr.nr.z, kr.nr.w};
 #pragma unroll
       for (int g = 0; g < NGK; ++g) {
-        const half8 dk = __builtin_bit_cast(half8, kr.kd[g]);
-        const half8 zk = __builtin_bit_cast(half8, kr.kz[g]);
         float dz[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) dz[i] = (float)dk[i] * (float)zk[i];
+        mix_mul8(kr.kd[g], kr.kz[g], dz);
         float bias[HP];
 #pragma unroll
         for (int s = 0; s < HP; ++s) {
@@ -579,8 +616,9 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
           }
 #pragma unroll
           for (int s = 0; s < HP; ++s) {
-            S[s][T] = (float)nt[T] * fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]);
-            S[s][T + 1] = (float)nt[T + 1] * fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]);
+            // T is even: tokens T, T+1 are the two halves of norm word T/2
+            S[s][T] = mix_scale<0>(fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
+            S[s][T + 1] = mix_scale<1>(fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
           }
         }
       }
@@ -610,9 +648,10 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     }
 
     // ---- scale of the value operand for this page: Delta_v * 2^xv < 2^13 ----
-    float dmax = 0.0f;
+    uint4 dm = vr.vd[0];
 #pragma unroll
-    for (int g = 0; g < NGV; ++g) dmax = fmaxf(dmax, max8_halves(vr.vd[g]));
+    for (int g = 1; g < NGV; ++g) dm = pk_max4(dm, vr.vd[g]);
+    float dmax = max8_halves(dm);
     dmax = row16_max(dmax);   // the 16 lanes of a head group cover all 128 tokens
     int exv = 0;
     (void)frexpf(dmax, &exv);
@@ -647,11 +686,8 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       for (int T = 0; T < 8; ++T) pc[s][T] = S[s][T] * (vsc0[T] * pscale);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
-      const half8 dv = __builtin_bit_cast(half8, vr.vd[g]);
-      const half8 zv = __builtin_bit_cast(half8, vr.vz[g]);
       float dz[8];
-#pragma unroll
-      for (int T = 0; T < 8; ++T) dz[T] = (float)dv[T] * (float)zv[T];
+      mix_mul8(vr.vd[g], vr.vz[g], dz);
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
         float acc_b = 0.0f;

@@ -153,28 +153,46 @@ template <int HI> __device__ __forceinline__ float mix_scale(float x, uint32_t h
   return r;
 }
 
+// The unpack masks live in scalar registers: an AND with a scalar operand has the short
+// 32-bit encoding, the same AND with a 32-bit literal the long one, and a wave issues short
+// encodings at a higher rate (measured: 4 against 6 cycles per instruction and wave).
+template <int BITS> struct Masks {
+  uint32_t m0, m1, m2;
+  __device__ __forceinline__ void init() {
+    if (BITS == 2) {
+      asm volatile("s_mov_b32 %0, 0x00300030" : "=s"(m0));
+      asm volatile("s_mov_b32 %0, 0x00C000C0" : "=s"(m1));
+      asm volatile("s_mov_b32 %0, 0x03000300" : "=s"(m2));
+    } else {
+      asm volatile("s_mov_b32 %0, 0x003C003C" : "=s"(m0));
+      asm volatile("s_mov_b32 %0, 0x03C003C0" : "=s"(m1));
+      m2 = 0;
+    }
+  }
+};
+
 // One 32-code chunk -> the four B-operand vectors (k-steps 0..3) of a 16x16x32 MFMA.
 template <int BITS> struct Chunk;
 template <> struct Chunk<2> {
   uint32_t w[2];
-  __device__ __forceinline__ void operands(u32x4 (&b)[4]) const {
+  __device__ __forceinline__ void operands(u32x4 (&b)[4], const Masks<2>& m) const {
 #pragma unroll
     for (int d = 0; d < 2; ++d) {
       // bit pairs 0,1 via << 4 (-> positions 4, 6), pairs 2,3,4 in place, pairs 5,6,7 via >> 6
       const uint32_t x = w[d], y = x >> 6, z = x << 4;
-      b[2 * d] = (u32x4){z & 0x00300030u, z & 0x00C000C0u, x & 0x00300030u, x & 0x00C000C0u};
-      b[2 * d + 1] = (u32x4){x & 0x03000300u, y & 0x00300030u, y & 0x00C000C0u, y & 0x03000300u};
+      b[2 * d] = (u32x4){z & m.m0, z & m.m1, x & m.m0, x & m.m1};
+      b[2 * d + 1] = (u32x4){x & m.m2, y & m.m0, y & m.m1, y & m.m2};
     }
   }
 };
 template <> struct Chunk<4> {
   uint32_t w[4];
-  __device__ __forceinline__ void operands(u32x4 (&b)[4]) const {
+  __device__ __forceinline__ void operands(u32x4 (&b)[4], const Masks<4>& m) const {
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       // nibbles 0,1 via << 2 (-> bit offsets 2, 6), nibbles 2,3 via >> 6
       const uint32_t x = w[d], y = x >> 6, z = x << 2;
-      b[d] = (u32x4){z & 0x003C003Cu, z & 0x03C003C0u, y & 0x003C003Cu, y & 0x03C003C0u};
+      b[d] = (u32x4){z & m.m0, z & m.m1, y & m.m0, y & m.m1};
     }
   }
 };
@@ -219,43 +237,64 @@ template <> struct TilePair<4> {
   }
 };
 
-// What one wave needs of one page, in registers.  Key side and value side are separate
-// sets: each is reloaded for the next page as soon as the current page is done with it,
-// so only one copy of each is ever live.
+// The five buffer resources of one page (wave-uniform, scalar registers).
+struct PageRsrc {
+  __amdgpu_buffer_rsrc_t kcodes, kmeta, knorm, vcodes, vmeta;
+  __device__ __forceinline__ void make(const DecodeParams& P, size_t pgi, bool valid) {
+    kcodes = page_rsrc(P.c.k_codes, pgi, P.g.k_codes_bytes, valid);
+    kmeta = page_rsrc(P.c.k_meta, pgi, P.g.k_meta_bytes, valid);
+    knorm = page_rsrc(P.c.k_norms, pgi, P.g.k_norms_bytes, valid);
+    vcodes = page_rsrc(P.c.v_codes, pgi, P.g.v_codes_bytes, valid);
+    vmeta = page_rsrc(P.c.v_meta, pgi, P.g.v_meta_bytes, valid);
+  }
+};
+
+// What one wave needs of one page, in registers, single-buffered: every register is
+// reloaded for the wave's next page right after its last use for the current one, so each
+// load has a whole iteration to arrive and only one copy of a page is ever live.
 template <int BITS, int NGK> struct KeyRegs {
+  static constexpr int PB = 2 * chunk_bytes(BITS);  // bytes of a lane's tile pair
   TilePair<BITS> kc[4];
   uint4 kd[NGK], kz[NGK];  // key Delta / zero of positions 8n..8n+7 (operand order)
   uint4 nr;                // norms of tokens 16*T+n, T = 0..7
-  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane, bool valid) {
-    const int n = lane & 15, q4 = lane >> 4;
-    const __amdgpu_buffer_rsrc_t kcodes = page_rsrc(P.c.k_codes, pgi, P.g.k_codes_bytes, valid);
-    const __amdgpu_buffer_rsrc_t kmeta = page_rsrc(P.c.k_meta, pgi, P.g.k_meta_bytes, valid);
-    const __amdgpu_buffer_rsrc_t knorm = page_rsrc(P.c.k_norms, pgi, P.g.k_norms_bytes, valid);
-    constexpr int PB = 2 * chunk_bytes(BITS);  // bytes of a lane's tile pair
+  __device__ __forceinline__ void load_codes(const PageRsrc& r, int tp, int lane) {
+    kc[tp].load(r.kcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB);
+  }
+  __device__ __forceinline__ void load_meta(const PageRsrc& r, int g, int lane) {
+    kd[g] = buf_load16(r.kmeta, (g * D + 8 * (lane & 15)) * 2);
+    kz[g] = buf_load16(r.kmeta, ((NGK + g) * D + 8 * (lane & 15)) * 2);
+  }
+  __device__ __forceinline__ void load_norm(const PageRsrc& r, int lane) {
+    nr = buf_load16(r.knorm, 8 * (lane & 15) * 2);
+  }
+  __device__ __forceinline__ void load(const PageRsrc& r, int lane) {
 #pragma unroll
-    for (int tp = 0; tp < 4; ++tp) kc[tp].load(kcodes, (tp * 64 + n * 4 + q4) * PB);
+    for (int tp = 0; tp < 4; ++tp) load_codes(r, tp, lane);
 #pragma unroll
-    for (int g = 0; g < NGK; ++g) {
-      kd[g] = buf_load16(kmeta, (g * D + 8 * n) * 2);
-      kz[g] = buf_load16(kmeta, ((NGK + g) * D + 8 * n) * 2);
-    }
-    nr = buf_load16(knorm, 8 * n * 2);
+    for (int g = 0; g < NGK; ++g) load_meta(r, g, lane);
+    load_norm(r, lane);
   }
 };
 template <int BITS, int NGV> struct ValRegs {
+  static constexpr int PB = 2 * chunk_bytes(BITS);
   TilePair<BITS> vc[4];
   uint4 vd[NGV], vz[NGV];  // value Delta / zero of tokens 16*T+n
-  __device__ __forceinline__ void load(const DecodeParams& P, size_t pgi, int lane, bool valid) {
-    const int n = lane & 15, q4 = lane >> 4;
-    const __amdgpu_buffer_rsrc_t vcodes = page_rsrc(P.c.v_codes, pgi, P.g.v_codes_bytes, valid);
-    const __amdgpu_buffer_rsrc_t vmeta = page_rsrc(P.c.v_meta, pgi, P.g.v_meta_bytes, valid);
-    constexpr int PB = 2 * chunk_bytes(BITS);
+  __device__ __forceinline__ void load_codes(const PageRsrc& r, int tp, int lane) {
+    vc[tp].load(r.vcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB);
+  }
+  __device__ __forceinline__ void load_delta(const PageRsrc& r, int g, int lane) {
+    vd[g] = buf_load16(r.vmeta, (g * R + 8 * (lane & 15)) * 2);
+  }
+  __device__ __forceinline__ void load_zero(const PageRsrc& r, int g, int lane) {
+    vz[g] = buf_load16(r.vmeta, ((NGV + g) * R + 8 * (lane & 15)) * 2);
+  }
+  __device__ __forceinline__ void load(const PageRsrc& r, int lane) {
 #pragma unroll
-    for (int tp = 0; tp < 4; ++tp) vc[tp].load(vcodes, (tp * 64 + n * 4 + q4) * PB);
+    for (int tp = 0; tp < 4; ++tp) load_codes(r, tp, lane);
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
-      vd[g] = buf_load16(vmeta, (g * R + 8 * n) * 2);
-      vz[g] = buf_load16(vmeta, ((NGV + g) * R + 8 * n) * 2);
+      load_delta(r, g, lane);
+      load_zero(r, g, lane);
     }
   }
 };
@@ -383,9 +422,10 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   KeyRegs<BITS, NGK> kr;
   ValRegs<BITS, NGV> vr;
   {
-    const size_t pgi = (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh;
-    kr.load(P, pgi, lane, pg_first < n_pages);
-    vr.load(P, pgi, lane, pg_first < n_pages);
+    PageRsrc first;
+    first.make(P, (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh, pg_first < n_pages);
+    kr.load(first, lane);
+    vr.load(first, lane);
   }
   const size_t rb = ((size_t)b * Hkv + kvh) * R;
   const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
@@ -550,6 +590,8 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   for (int T = 0; T < 8; ++T)
     vsc0[T] = ldexpf(1.0f, slot_bitpos_min(BITS) - slot_bitpos(BITS, n >> 2, T));
 
+  Masks<BITS> masks;
+  masks.init();
   _Float16(*A_tab)[TABW] = s_A[wave];
   _Float16(*P_tab)[TABW] = s_P[wave];
 
@@ -568,7 +610,8 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     // entries past the wave's last page read as 0 (a valid page index) and the load is void
     const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
                               : __builtin_amdgcn_readlane(tabn, 0);
-    const size_t next_pgi = (size_t)phys * Hkv + kvh;
+    PageRsrc nx;   // the wave's next page
+    nx.make(P, (size_t)phys * Hkv + kvh, has_next);
 
     // ---- q K^T ----
     float S[HP][8];
@@ -593,6 +636,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
             *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
           }
         }
+        kr.load_meta(nx, g, lane);
         wave_lds_fence();
         half8 areg[4];
 #pragma unroll
@@ -604,8 +648,9 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
           // two token tiles at a time: independent accumulators keep the MFMA pipe busy
           const int T = g * TPG + tt;
           u32x4 b0[4], b1[4];
-          kr.kc[T >> 1].chunk(0).operands(b0);
-          kr.kc[T >> 1].chunk(1).operands(b1);
+          kr.kc[T >> 1].chunk(0).operands(b0, masks);
+          kr.kc[T >> 1].chunk(1).operands(b1, masks);
+          kr.load_codes(nx, T >> 1, lane);
           float4v acc0 = (float4v){0.0f, 0.0f, 0.0f, 0.0f}, acc1 = acc0;
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) {
@@ -623,8 +668,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
         }
       }
     }
-    // the key registers are free: fetch the next page's key side behind the value work
-    kr.load(P, next_pgi, lane, has_next);
+    kr.load_norm(nx, lane);
 
     // ---- online softmax (per head slot; the 16 lanes of a group share a head) ----
     float alpha[HP];
@@ -688,6 +732,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
     for (int g = 0; g < NGV; ++g) {
       float dz[8];
       mix_mul8(vr.vd[g], vr.vz[g], dz);
+      vr.load_zero(nx, g, lane);
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
         float acc_b = 0.0f;
@@ -702,6 +747,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
           *reinterpret_cast<uint4*>(&P_tab[row_hi(h) + 1][8 * n]) = lo;
         }
       }
+      vr.load_delta(nx, g, lane);
       wave_lds_fence();
       half8 preg[4];
 #pragma unroll
@@ -712,8 +758,9 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       for (int cc = 0; cc < CPG; cc += 2) {
         const int ct = g * CPG + cc;
         u32x4 b0[4], b1[4];
-        vr.vc[ct >> 1].chunk(0).operands(b0);
-        vr.vc[ct >> 1].chunk(1).operands(b1);
+        vr.vc[ct >> 1].chunk(0).operands(b0, masks);
+        vr.vc[ct >> 1].chunk(1).operands(b1, masks);
+        vr.load_codes(nx, ct >> 1, lane);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
@@ -723,7 +770,6 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
         }
       }
     }
-    vr.load(P, next_pgi, lane, has_next);
   }
   }
 

@@ -9,29 +9,29 @@
 // depend on whether a multiply-add was fused).
 //
 // Work decomposition: one workgroup of 256 threads per (sequence, kv head, block of
-// R=128 pending tokens).  Thread (slot = tid/16, sub = tid%16) owns channels
-// 8*sub..8*sub+7 of token 16*pass+slot for pass = 0..7, so
-//   - the 128-point Hadamard butterfly runs 3 stages in registers and 4 stages
-//     across the 16 lanes of a token (lane bit s <-> channel bit 3+s),
-//   - the token norm is a 16-lane butterfly all-reduce,
-//   - per-channel min/max over tokens reduce over passes (registers), over the 4
-//     token slots of a wave (lane bits 4,5) and over the 4 waves (LDS),
-//   - per-token value min/max reduce over 8 registers and 4|8|16 lanes.
-// Codes are staged in LDS as the page image and leave with 16-byte coalesced stores.
+// R=128 pending tokens).  A thread owns 8 channels (channel group cg) of token
+// 16*pass+slot for pass = 0..7; the 16 lanes of a DPP row share a token, so
+//   - the 128-point Hadamard butterfly runs 3 stages in registers and 4 stages across the
+//     row.  Lanes are labelled so that the partner of every stage is one DPP control
+//     (cg^1, cg^2: quad permutes; cg^4: half-row mirror; cg^8: row rotate by 8): no
+//     LDS-crossbar shuffles, and a butterfly is "partner + (own with the sign bit flipped
+//     in the upper lane)", which is the same fp32 add/sub the format prescribes,
+//   - the token norm is a 16-lane butterfly all-reduce over the same partners,
+//   - per-channel min/max over tokens reduce over passes (packed fp16 registers), over the
+//     4 token slots of a wave and over the 4 waves (LDS); each channel's Eq. 3-4 parameters
+//     are computed once and handed to the 16 token slots through LDS,
+//   - per-token value min/max reduce over 8 registers and 4|8|16 lanes of the row.
+// Rotated keys are held as packed fp16 (that is what they are), values in their input
+// type: about half the registers of an fp32 copy, which doubles the resident waves.
+// A code is clamp(rint(x/Delta), -z, qmax-z) + z; codes of one packed word are summed in
+// fp32 with their place values (exact: small integers) and converted once.  Both code
+// images are built in LDS in their final page layout and leave with 16-byte stores.
 #include "oscar_common.h"
 
 namespace {
 
 constexpr int D = OSCAR_D;
 constexpr int R = OSCAR_R;
-constexpr int VROW_PAD = R + 4;  // LDS row stride (bytes) of the value code bytes
-
-// Staging position of value code (channel c, token t): rows are channels, columns are
-// tokens in chunk order (q4 = t%4 major, then k-step, then element), skewed per 32 rows to
-// spread LDS banks.
-__device__ __forceinline__ int vimg_index(int c, int t) {
-  return c * VROW_PAD + (c / 32) * 4 + (t % 4) * 32 + ((t / 4) % 4) * 8 + t / 16;
-}
 
 struct AppendParams {
   const void* k;
@@ -43,46 +43,64 @@ struct AppendParams {
   uint32_t flags;
 };
 
-template <typename IO> __device__ __forceinline__ void load8(const IO* p, float (&x)[8]);
-template <> __device__ __forceinline__ void load8<float>(const float* p, float (&x)[8]) {
-  float4 a = reinterpret_cast<const float4*>(p)[0];
-  float4 b = reinterpret_cast<const float4*>(p)[1];
-  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-  x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-}
-template <> __device__ __forceinline__ void load8<__half>(const __half* p, float (&x)[8]) {
-  uint4 r = *reinterpret_cast<const uint4*>(p);
-  uint32_t w[4] = {r.x, r.y, r.z, r.w};
+// Eight consecutive elements of the caller's type, held raw (packed) in registers.
+template <typename IO> struct Raw8;
+template <> struct Raw8<float> {
+  uint4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = reinterpret_cast<const uint4*>(p)[0];
+    b = reinterpret_cast<const uint4*>(p)[1];
+  }
+  __device__ __forceinline__ void load_halves(const __half* p) {   // 8 fp16 values, kept in a
+    a = *reinterpret_cast<const uint4*>(p);
+    b = a;
+  }
+  __device__ __forceinline__ void store(float* p) const {
+    reinterpret_cast<uint4*>(p)[0] = a;
+    reinterpret_cast<uint4*>(p)[1] = b;
+  }
+  __device__ __forceinline__ void widen(float (&x)[8]) const {
+    x[0] = __uint_as_float(a.x); x[1] = __uint_as_float(a.y);
+    x[2] = __uint_as_float(a.z); x[3] = __uint_as_float(a.w);
+    x[4] = __uint_as_float(b.x); x[5] = __uint_as_float(b.y);
+    x[6] = __uint_as_float(b.z); x[7] = __uint_as_float(b.w);
+  }
+};
+__device__ __forceinline__ void widen_halves(const uint4& r, float (&x)[8]) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     x[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
     x[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
   }
 }
-template <> __device__ __forceinline__ void load8<__hip_bfloat16>(const __hip_bfloat16* p,
-                                                                  float (&x)[8]) {
-  uint4 r = *reinterpret_cast<const uint4*>(p);
-  uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    x[2 * i] = __uint_as_float(w[i] << 16);
-    x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+template <> struct Raw8<__half> {
+  uint4 a;
+  __device__ __forceinline__ void load(const __half* p) { a = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void load_halves(const __half* p) { load(p); }
+  __device__ __forceinline__ void store(__half* p) const { *reinterpret_cast<uint4*>(p) = a; }
+  __device__ __forceinline__ void widen(float (&x)[8]) const { widen_halves(a, x); }
+};
+template <> struct Raw8<__hip_bfloat16> {
+  uint4 a;
+  __device__ __forceinline__ void load(const __hip_bfloat16* p) {
+    a = *reinterpret_cast<const uint4*>(p);
   }
-}
-
-template <typename IO> __device__ __forceinline__ void copy8(IO* dst, const IO* src);
-template <> __device__ __forceinline__ void copy8<float>(float* dst, const float* src) {
-  reinterpret_cast<float4*>(dst)[0] = reinterpret_cast<const float4*>(src)[0];
-  reinterpret_cast<float4*>(dst)[1] = reinterpret_cast<const float4*>(src)[1];
-}
-template <> __device__ __forceinline__ void copy8<__half>(__half* dst, const __half* src) {
-  *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
-}
-template <>
-__device__ __forceinline__ void copy8<__hip_bfloat16>(__hip_bfloat16* dst,
-                                                      const __hip_bfloat16* src) {
-  *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
-}
+  __device__ __forceinline__ void load_halves(const __half* p) {
+    a = *reinterpret_cast<const uint4*>(p);
+  }
+  __device__ __forceinline__ void store(__hip_bfloat16* p) const {
+    *reinterpret_cast<uint4*>(p) = a;
+  }
+  __device__ __forceinline__ void widen(float (&x)[8]) const {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
 
 // Keeps a value in a VGPR across an empty asm: stops the compiler from folding the
 // fp32 multiply and the fp16 conversion below into one mixed-precision instruction that
@@ -96,11 +114,29 @@ __device__ __forceinline__ uint32_t half_bits(float x) {
   return (uint32_t)__half_as_ushort(__float2half_rn(x));
 }
 
+// Value of the lane whose channel group differs in bit STAGE (0..3), inside the 16-lane
+// row of a token.  Row lane r holds channel group cg = (r0^r2) | (r1^r2)<<1 | r2<<2 | r3<<3.
+template <int STAGE> __device__ __forceinline__ float partner(float v) {
+  constexpr int ctrl = STAGE == 0 ? 0xB1     // quad_perm [1,0,3,2]: r ^ 1
+                     : STAGE == 1 ? 0x4E     // quad_perm [2,3,0,1]: r ^ 2
+                     : STAGE == 2 ? 0x141    // row_half_mirror:     r ^ 7
+                                  : 0x128;   // row_ror:8:           r ^ 8
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
+}
+__device__ __forceinline__ int channel_group_of_row_lane(int r) {
+  const int b2 = (r >> 2) & 1;
+  return ((r ^ b2) & 1) | ((((r >> 1) ^ b2) & 1) << 1) | (b2 << 2) | (r & 8);
+}
+
 // Key transform of 8 channels of one token held by 16 cooperating lanes:
 // K_h = H(k)/sqrt(128), n = ||K_h||_2 rounded to the metadata type, K_u = K_h / n
-// rounded to fp16.  Butterfly stage h pairs (i, i|h): lower <- a+b, upper <- a-b.
+// rounded to fp16 (returned packed).  Butterfly stage h pairs (i, i|h): lower <- a+b,
+// upper <- a-b; across lanes that is partner + own, with the own value negated in the
+// upper lane (sgn[stage] = sign bit there, 0 in the lower lane).
 template <typename META>
-__device__ __forceinline__ void key_transform8(float (&x)[8], int sub, float& n_st) {
+__device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&sgn)[4],
+                                                float& n_st) {
 #pragma unroll
   for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
@@ -113,14 +149,13 @@ __device__ __forceinline__ void key_transform8(float (&x)[8], int sub, float& n_
     }
   }
 #pragma unroll
-  for (int m = 1; m < 16; m <<= 1) {
-    const bool upper = (sub & m) != 0;
+  for (int i = 0; i < 8; ++i) x[i] = partner<0>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[0]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float y = __shfl_xor(x[i], m, 64);
-      x[i] = upper ? (y - x[i]) : (x[i] + y);
-    }
-  }
+  for (int i = 0; i < 8; ++i) x[i] = partner<1>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[1]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = partner<2>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[2]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = partner<3>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[3]);
   const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
   float t[8];
 #pragma unroll
@@ -130,14 +165,19 @@ __device__ __forceinline__ void key_transform8(float (&x)[8], int sub, float& n_
   }
   // balanced tree, adjacent pairs first
   float s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) s = s + __shfl_xor(s, m, 64);
+  s = s + partner<0>(s);
+  s = s + partner<1>(s);
+  s = s + partner<2>(s);
+  s = s + partner<3>(s);
   float n = sqrtf(s);
   float nf = round_meta<META>(n);
   float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
+  uint32_t w[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = __half2float(__float2half_rn(pin_f32(x[i] * inv)));
+  for (int i = 0; i < 4; ++i)
+    w[i] = half_bits(pin_f32(x[2 * i] * inv)) | (half_bits(pin_f32(x[2 * i + 1] * inv)) << 16);
   n_st = nf;
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // Eq. 3-4 parameters of one group, rounded to storage before use.
@@ -154,25 +194,26 @@ __device__ __forceinline__ void quant_params(float mn, float mx, float& df, floa
   z = round_meta<META>(rintf(-mn * rd));
 }
 
-template <int BITS> __device__ __forceinline__ uint32_t quant_code(float x, float rd, float z) {
-  const float qmax = (float)((1 << BITS) - 1);
-  float c = rintf(x * rd) + z;
-  c = fminf(fmaxf(c, 0.0f), qmax);
-  return (uint32_t)c;
+// packed fp16 min / max (finite inputs); volatile: plain asm blocks of this kind have been
+// seen to be mis-scheduled
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm volatile("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm volatile("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float half_of(uint32_t w, int hi) {
+  return __half2float(__ushort_as_half((unsigned short)(hi ? (w >> 16) : (w & 0xffffu))));
 }
 
-template <typename M> __device__ __forceinline__ void store_meta8(M* dst, const float (&v)[8]);
-template <> __device__ __forceinline__ void store_meta8<float>(float* dst, const float (&v)[8]) {
-  reinterpret_cast<float4*>(dst)[0] = make_float4(v[0], v[1], v[2], v[3]);
-  reinterpret_cast<float4*>(dst)[1] = make_float4(v[4], v[5], v[6], v[7]);
-}
-template <> __device__ __forceinline__ void store_meta8<__half>(__half* dst, const float (&v)[8]) {
-  uint4 o;
-  o.x = half_bits(v[0]) | (half_bits(v[1]) << 16);
-  o.y = half_bits(v[2]) | (half_bits(v[3]) << 16);
-  o.z = half_bits(v[4]) | (half_bits(v[5]) << 16);
-  o.w = half_bits(v[6]) | (half_bits(v[7]) << 16);
-  *reinterpret_cast<uint4*>(dst) = o;
+// clamp(rint(x * rd) + z, 0, qmax) - z, i.e. the code minus its zero-point (an integer in
+// fp32): lo = -z, hi = qmax - z.
+__device__ __forceinline__ float code_minus_zero(float x, float rd, float lo, float hi) {
+  return __builtin_amdgcn_fmed3f(rintf(x * rd), lo, hi);
 }
 
 struct SeqPlan {
@@ -202,21 +243,38 @@ __device__ __forceinline__ SeqPlan plan_sequence(const AppendParams& P, int b) {
   return s;
 }
 
+template <int BITS> __device__ __forceinline__ constexpr float place_value(int i) {
+  // 4^i (2-bit codes) or 16^i (4-bit codes)
+  float v = 1.0f;
+  for (int k = 0; k < i; ++k) v *= (float)(1 << BITS);
+  return v;
+}
+
 template <typename IO, typename META, int BITS, int KG>
 __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   constexpr int NGK = R / KG;        // key groups per page
   constexpr int PPG = KG / 16;       // passes per key group
+  constexpr float QMAX = (float)((1 << BITS) - 1);
+  constexpr int IMG = R * D * BITS / 8;   // bytes of one code image
 
-  __shared__ float s_red[NGK][4][D][2];
-  __shared__ __align__(16) uint8_t s_kimg[R * D * BITS / 8];     // key-code page image
-  __shared__ __align__(16) uint8_t s_vimg[D * VROW_PAD + 64];    // value codes, one per byte
+  struct MinMax {
+    uint4 mn, mx;   // packed fp16, the 8 channels of a channel group
+  };
+  __shared__ __align__(16) MinMax s_red[NGK][4][16];   // [group][wave][channel group]
+  __shared__ __align__(16) float4 s_par[NGK][D];       // per channel: 1/Delta, -z, qmax-z, z*place
+  __shared__ __align__(16) uint8_t s_kimg[IMG];        // key-code page image
+  __shared__ __align__(16) uint8_t s_vimg[IMG];        // value-code page image
   __shared__ __align__(16) META s_vmeta[2][4][R];
   __shared__ __align__(16) META s_norm[R];
 
   const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int slot = tid >> 4, sub = tid & 15;
+  const int slot = tid >> 4;                            // token of a pass
+  const int cg = channel_group_of_row_lane(tid & 15);   // channels 8*cg .. 8*cg+7
   const int Hkv = P.c.cfg.n_kv_heads;
+  uint32_t sgn[4];
+#pragma unroll
+  for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
 
   const SeqPlan sp = plan_sequence(P, b);
   do {  // one pass; "break" = this workgroup has nothing (more) to do
@@ -236,37 +294,41 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   IO* res_v = reinterpret_cast<IO*>(P.c.res_v) + res_base * D;
   META* res_norm = reinterpret_cast<META*>(P.c.res_norm) + res_base;
 
-  // ---- phase 1: gather the block (old residual tokens first, then new tokens) ----
-  float u[8][8], vv[8][8], nrm[8];
+  // ---- phase 1: gather the block (old residual tokens first, then new tokens) and
+  // transform the new keys; keys end up as packed fp16 K_u, values stay raw ----
+  uint4 ku[8];
+  Raw8<IO> vraw[8];
+  float nrm[8];
   if (do_block) {
+    Raw8<IO> kraw[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const int pi = blk * R + p * 16 + slot;  // index among pending tokens
       if (pi < sp.r0) {
-        load8<__half>(res_k + (size_t)pi * D + sub * 8, u[p]);
+        kraw[p].load_halves(res_k + (size_t)pi * D + cg * 8);
         nrm[p] = to_f32<META>(res_norm[pi]);
-        load8<IO>(res_v + (size_t)pi * D + sub * 8, vv[p]);
+        vraw[p].load(res_v + (size_t)pi * D + cg * 8);
       } else {
         const size_t ti = (size_t)(pi - sp.r0);
-        const size_t off = (((size_t)b * P.T + ti) * Hkv + kvh) * D + sub * 8;
-        load8<IO>(knew + off, u[p]);
-        load8<IO>(vnew + off, vv[p]);
+        const size_t off = (((size_t)b * P.T + ti) * Hkv + kvh) * D + cg * 8;
+        kraw[p].load(knew + off);
+        vraw[p].load(vnew + off);
+        nrm[p] = 0.0f;
       }
     }
-    // the branch above is uniform per 16-lane token group; transform where needed
+    // the branch above is uniform per 16-lane token row; every row runs the transform (its
+    // result is dropped for tokens that came from the residual, which are K_u already)
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      const int pi = blk * R + p * 16 + slot;
-      float x[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = u[p][i];
-      float nn;
-      key_transform8<META>(x, sub, nn);
-      if (pi >= sp.r0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) u[p][i] = x[i];
-        nrm[p] = nn;
-      }
+      const bool old = blk * R + p * 16 + slot < sp.r0;
+      float x[8], nn;
+      kraw[p].widen(x);
+      const uint4 nu = key_transform8<META>(x, sgn, nn);
+      ku[p].x = old ? kraw[p].a.x : nu.x;
+      ku[p].y = old ? kraw[p].a.y : nu.y;
+      ku[p].z = old ? kraw[p].a.z : nu.z;
+      ku[p].w = old ? kraw[p].a.w : nu.w;
+      nrm[p] = old ? nrm[p] : nn;
     }
   }
   __syncthreads();  // every read of the old residual precedes the tail write below
@@ -279,20 +341,18 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     for (int i0 = 0; i0 < cnt; i0 += 16) {
       const int i = i0 + slot;
       const int ic = i < cnt ? i : cnt - 1;
-      const size_t off = (((size_t)b * P.T + (size_t)(src0 + ic)) * Hkv + kvh) * D + sub * 8;
+      const size_t off = (((size_t)b * P.T + (size_t)(src0 + ic)) * Hkv + kvh) * D + cg * 8;
+      Raw8<IO> kin, vin;
+      kin.load(knew + off);
+      vin.load(vnew + off);
       float x[8], nn;
-      load8<IO>(knew + off, x);
-      key_transform8<META>(x, sub, nn);
+      kin.widen(x);
+      const uint4 nu = key_transform8<META>(x, sgn, nn);
       if (i < cnt) {
         const int ds = dst0 + i;
-        uint4 o;
-        o.x = half_bits(x[0]) | (half_bits(x[1]) << 16);
-        o.y = half_bits(x[2]) | (half_bits(x[3]) << 16);
-        o.z = half_bits(x[4]) | (half_bits(x[5]) << 16);
-        o.w = half_bits(x[6]) | (half_bits(x[7]) << 16);
-        *reinterpret_cast<uint4*>(res_k + (size_t)ds * D + sub * 8) = o;
-        copy8<IO>(res_v + (size_t)ds * D + sub * 8, vnew + off);
-        if (sub == 0) res_norm[ds] = from_f32<META>(nn);
+        *reinterpret_cast<uint4*>(res_k + (size_t)ds * D + cg * 8) = nu;
+        vin.store(res_v + (size_t)ds * D + cg * 8);
+        if (cg == 0) res_norm[ds] = from_f32<META>(nn);
       }
     }
   }
@@ -308,144 +368,175 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   uint8_t* o_vcodes = reinterpret_cast<uint8_t*>(P.c.v_codes) + pg * P.g.v_codes_bytes;
   META* o_vmeta = reinterpret_cast<META*>(reinterpret_cast<uint8_t*>(P.c.v_meta) + pg * P.g.v_meta_bytes);
 
-  // keys: per-channel min/max over the tokens of each group
+  // keys: per-channel min/max over the tokens of each group: passes, then the 4 token rows
+  // of the wave, then (through LDS) the 4 waves
 #pragma unroll
   for (int gk = 0; gk < NGK; ++gk) {
+    uint32_t mn[4] = {ku[gk * PPG].x, ku[gk * PPG].y, ku[gk * PPG].z, ku[gk * PPG].w};
+    uint32_t mx[4] = {mn[0], mn[1], mn[2], mn[3]};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float mn = u[gk * PPG][e], mx = mn;
+    for (int p = 1; p < PPG; ++p) {
+      const uint4 q = ku[gk * PPG + p];
+      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-      for (int p = 1; p < PPG; ++p) {
-        mn = fminf(mn, u[gk * PPG + p][e]);
-        mx = fmaxf(mx, u[gk * PPG + p][e]);
-      }
-      mn = fminf(mn, __shfl_xor(mn, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mn = fminf(mn, __shfl_xor(mn, 32, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      if (lane < 16) {
-        s_red[gk][wave][sub * 8 + e][0] = mn;
-        s_red[gk][wave][sub * 8 + e][1] = mx;
+      for (int j = 0; j < 4; ++j) {
+        mn[j] = pk_min_f16(mn[j], w[j]);
+        mx[j] = pk_max_f16(mx[j], w[j]);
       }
     }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      mn[j] = pk_min_f16(mn[j], (uint32_t)__shfl_xor((int)mn[j], 16, 64));
+      mx[j] = pk_max_f16(mx[j], (uint32_t)__shfl_xor((int)mx[j], 16, 64));
+      mn[j] = pk_min_f16(mn[j], (uint32_t)__shfl_xor((int)mn[j], 32, 64));
+      mx[j] = pk_max_f16(mx[j], (uint32_t)__shfl_xor((int)mx[j], 32, 64));
+    }
+    if (lane < 16) {
+      s_red[gk][wave][cg].mn = make_uint4(mn[0], mn[1], mn[2], mn[3]);
+      s_red[gk][wave][cg].mx = make_uint4(mx[0], mx[1], mx[2], mx[3]);
+    }
   }
-  if (sub == 0) {
+  if (cg == 0) {
 #pragma unroll
     for (int p = 0; p < 8; ++p) s_norm[tok_meta_pos(p * 16 + slot)] = from_f32<META>(nrm[p]);
   }
   __syncthreads();
 
+  // Eq. 3-4 parameters, once per channel and group: thread (slot < 8, cg) takes channel
+  // 8*cg + slot, stores Delta and z (operand order, see kmeta_pos_of_chan) and leaves what
+  // the coders need in LDS
+  if (slot < 8) {
+    const int e = slot, c = 8 * cg + e;
+#pragma unroll
+    for (int gk = 0; gk < NGK; ++gk) {
+      uint32_t mnw = 0, mxw = 0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t* rp = reinterpret_cast<const uint32_t*>(&s_red[gk][w][cg]);
+        const uint32_t a = rp[e >> 1], bb = rp[4 + (e >> 1)];
+        mnw = w == 0 ? a : pk_min_f16(mnw, a);
+        mxw = w == 0 ? bb : pk_max_f16(mxw, bb);
+      }
+      float df, rd, z;
+      quant_params<META, BITS>(half_of(mnw, e & 1), half_of(mxw, e & 1), df, rd, z);
+      // place value of this channel's code inside its packed word (4-bit: two 16-bit halves)
+      const float place = ldexpf(1.0f, BITS * ((BITS == 2) ? e : (e & 3)));
+      s_par[gk][c] = make_float4(rd, -z, QMAX - z, z * place);
+      const int pos = kmeta_pos_of_chan(BITS, c);
+      o_kmeta[(size_t)gk * D + pos] = from_f32<META>(df);
+      o_kmeta[(size_t)(NGK + gk) * D + pos] = from_f32<META>(z);
+    }
+  }
+  __syncthreads();
+
+  // key codes: a token's 8 codes of this channel group form one 16-bit (2-bit codes) or
+  // 32-bit (4-bit codes) piece of chunk (tile = tok/16, n = tok%16, q4 = cg/4)
 #pragma unroll
   for (int gk = 0; gk < NGK; ++gk) {
-    float dfa[8], za[8], rda[8];
+    float rd[8], lo[8], hi[8], zs0 = 0.0f, zs1 = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float mn = s_red[gk][0][sub * 8 + e][0], mx = s_red[gk][0][sub * 8 + e][1];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) {
-        mn = fminf(mn, s_red[gk][w][sub * 8 + e][0]);
-        mx = fmaxf(mx, s_red[gk][w][sub * 8 + e][1]);
-      }
-      quant_params<META, BITS>(mn, mx, dfa[e], rda[e], za[e]);
-    }
-    if (slot == 0) {
-      // Delta / zero in operand order (see kmeta_pos_of_chan)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int pos = kmeta_pos_of_chan(BITS, sub * 8 + e);
-        o_kmeta[(size_t)gk * D + pos] = from_f32<META>(dfa[e]);
-        o_kmeta[(size_t)(NGK + gk) * D + pos] = from_f32<META>(za[e]);
-      }
+      const float4 q = s_par[gk][8 * cg + e];
+      rd[e] = q.x;
+      lo[e] = q.y;
+      hi[e] = q.z;
+      if (BITS == 2 || e < 4) zs0 += q.w;
+      else zs1 += q.w;
     }
 #pragma unroll
     for (int p = gk * PPG; p < (gk + 1) * PPG; ++p) {
-      uint32_t w = 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) w |= quant_code<BITS>(u[p][e], rda[e], za[e]) << (e * BITS);
+      float x[8];
+      widen_halves(ku[p], x);
       const int tok = p * 16 + slot;
-      // chunk (tile = tok/16, n = tok%16, q4 = sub/4); this thread's 8 codes are numbers
-      // 8*(sub%4) .. +7 of the chunk
-      const int off = chunk_offset(BITS, tok / 16, tok % 16, sub / 4) + (sub % 4) * BITS;
+      const int off = chunk_offset(BITS, tok / 16, tok % 16, cg / 4) + (cg % 4) * BITS;
       if (BITS == 2) {
-        *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)w;
+        float w = zs0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          w = fmaf(code_minus_zero(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w);
+        *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)(uint32_t)w;
       } else {
-        *reinterpret_cast<uint32_t*>(&s_kimg[off]) = w;
+        float w0 = zs0, w1 = zs1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          w0 = fmaf(code_minus_zero(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w0);
+          w1 = fmaf(code_minus_zero(x[e + 4], rd[e + 4], lo[e + 4], hi[e + 4]), place_value<BITS>(e), w1);
+        }
+        *reinterpret_cast<uint32_t*>(&s_kimg[off]) = (uint32_t)w0 | ((uint32_t)w1 << 16);
       }
     }
   }
 
-  // values: per-token min/max over each group of v_group channels
-  const int lanes_per_vgroup = P.g.v_group / 8;  // 4, 8 or 16
+  // values: per-token min/max over each group of v_group channels (8 registers, then the
+  // 4 | 8 | 16 lanes of the group).  The thread's 8 tokens of one channel are the elements
+  // e = pass of k-step kk = slot/4 in chunk (tile = c/16, n = c%16, q4 = slot%4): even
+  // passes fill one byte (2-bit) / half-word (4-bit) of the piece, odd passes the other.
+  {
+    const int L = P.g.v_group / 8;  // lanes per value group: 4, 8 or 16
+    float wv0[8], wv1[8], zv0 = 0.0f, zv1 = 0.0f;
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    float mn = vv[p][0], mx = mn;
+    for (int e = 0; e < 8; ++e) wv0[e] = wv1[e] = 0.0f;
 #pragma unroll
-    for (int e = 1; e < 8; ++e) {
-      mn = fminf(mn, vv[p][e]);
-      mx = fmaxf(mx, vv[p][e]);
-    }
-    for (int m = 1; m < lanes_per_vgroup; m <<= 1) {
-      mn = fminf(mn, __shfl_xor(mn, m, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-    }
-    float df, rd, z;
-    quant_params<META, BITS>(mn, mx, df, rd, z);
-    const int tok = p * 16 + slot;
-    if ((sub & (lanes_per_vgroup - 1)) == 0) {
-      const int gv = sub / lanes_per_vgroup;
-      s_vmeta[0][gv][tok_meta_pos(tok)] = from_f32<META>(df);
-      s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(z);
-    }
+    for (int p = 0; p < 8; ++p) {
+      float v[8];
+      vraw[p].widen(v);
+      float mn = v[0], mx = v[0];
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      s_vimg[vimg_index(sub * 8 + e, tok)] = (uint8_t)quant_code<BITS>(vv[p][e], rd, z);
+      for (int e = 1; e < 8; ++e) {
+        mn = fminf(mn, v[e]);
+        mx = fmaxf(mx, v[e]);
+      }
+      if (L > 1) { mn = fminf(mn, partner<0>(mn)); mx = fmaxf(mx, partner<0>(mx)); }
+      if (L > 2) { mn = fminf(mn, partner<1>(mn)); mx = fmaxf(mx, partner<1>(mx)); }
+      if (L > 4) { mn = fminf(mn, partner<2>(mn)); mx = fmaxf(mx, partner<2>(mx)); }
+      if (L > 8) { mn = fminf(mn, partner<3>(mn)); mx = fmaxf(mx, partner<3>(mx)); }
+      float df, rd, z;
+      quant_params<META, BITS>(mn, mx, df, rd, z);
+      const int tok = p * 16 + slot;
+      if ((cg & (L - 1)) == 0) {
+        const int gv = cg / L;
+        s_vmeta[0][gv][tok_meta_pos(tok)] = from_f32<META>(df);
+        s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(z);
+      }
+      const float lo = -z, hi = QMAX - z;
+      const float pl = place_value<BITS>(p >> 1);
+      if ((p & 1) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wv0[e] = fmaf(code_minus_zero(v[e], rd, lo, hi), pl, wv0[e]);
+        zv0 = fmaf(z, pl, zv0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wv1[e] = fmaf(code_minus_zero(v[e], rd, lo, hi), pl, wv1[e]);
+        zv1 = fmaf(z, pl, zv1);
+      }
+    }
+    const int kk = slot >> 2, q4 = slot & 3;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = 8 * cg + e;
+      const uint32_t ev = (uint32_t)(wv0[e] + zv0), od = (uint32_t)(wv1[e] + zv1);
+      const int base = chunk_offset(BITS, c / 16, c % 16, q4);
+      if (BITS == 2) {
+        s_vimg[base + (kk >> 1) * 4 + (kk & 1)] = (uint8_t)ev;
+        s_vimg[base + (kk >> 1) * 4 + 2 + (kk & 1)] = (uint8_t)od;
+      } else {
+        *reinterpret_cast<uint32_t*>(&s_vimg[base + kk * 4]) = ev | (od << 16);
+      }
+    }
   }
   __syncthreads();
 
   // ---- phase 4: coalesced page stores ----
   {
-    const uint4* src = reinterpret_cast<const uint4*>(&s_kimg[0]);
-    uint4* dst = reinterpret_cast<uint4*>(o_kcodes);
-    constexpr int NV = R * D * BITS / 8 / 16;  // uint4 count: 256 (2-bit) or 512 (4-bit)
+    constexpr int NV = IMG / 16;  // uint4 count: 256 (2-bit) or 512 (4-bit)
+    const uint4* ksrc = reinterpret_cast<const uint4*>(&s_kimg[0]);
+    const uint4* vsrc = reinterpret_cast<const uint4*>(&s_vimg[0]);
+    uint4* kdst = reinterpret_cast<uint4*>(o_kcodes);
+    uint4* vdst = reinterpret_cast<uint4*>(o_vcodes);
 #pragma unroll
-    for (int i = tid; i < NV; i += 256) dst[i] = src[i];
-  }
-  {
-    // thread = (tile pair tp, n, q4): packs the chunks of channels 32*tp+n and 32*tp+16+n
-    const int tp = tid >> 6, n = (tid >> 2) & 15, q4 = tid & 3;
-    uint32_t outw[2][BITS];  // [channel of the pair][dword of the chunk]
-#pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-      const int c = 32 * tp + 16 * cc + n;
-      const uint32_t* row = reinterpret_cast<const uint32_t*>(&s_vimg[vimg_index(c, q4)]);
-#pragma unroll
-      for (int d = 0; d < BITS; ++d) outw[cc][d] = 0;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        // bytes of elements e = 0..3 and e = 4..7 of k-step kk
-        const uint32_t x0 = row[2 * kk], x1 = row[2 * kk + 1];
-        if (BITS == 2) {
-          const uint32_t ev = (x0 & 3u) | (((x0 >> 16) & 3u) << 2) | ((x1 & 3u) << 4) |
-                              (((x1 >> 16) & 3u) << 6);
-          const uint32_t od = ((x0 >> 8) & 3u) | (((x0 >> 24) & 3u) << 2) |
-                              (((x1 >> 8) & 3u) << 4) | (((x1 >> 24) & 3u) << 6);
-          // even elements -> code numbers 4*(kk%2)+r, odd elements -> 8 more
-          outw[cc][kk / 2] |= (ev << (8 * (kk % 2))) | (od << (16 + 8 * (kk % 2)));
-        } else {
-          const uint32_t ev = (x0 & 15u) | (((x0 >> 16) & 15u) << 4) | ((x1 & 15u) << 8) |
-                              (((x1 >> 16) & 15u) << 12);
-          const uint32_t od = ((x0 >> 8) & 15u) | (((x0 >> 24) & 15u) << 4) |
-                              (((x1 >> 8) & 15u) << 8) | (((x1 >> 24) & 15u) << 12);
-          outw[cc][kk] = ev | (od << 16);
-        }
-      }
-    }
-    uint8_t* dst = o_vcodes + (size_t)tid * 2 * chunk_bytes(BITS);
-    if (BITS == 2) {
-      *reinterpret_cast<uint4*>(dst) = make_uint4(outw[0][0], outw[0][1], outw[1][0], outw[1][1]);
-    } else {
-      reinterpret_cast<uint4*>(dst)[0] = make_uint4(outw[0][0], outw[0][1], outw[0][2], outw[0][3]);
-      reinterpret_cast<uint4*>(dst)[1] = make_uint4(outw[1][0], outw[1][1], outw[1][2], outw[1][3]);
+    for (int i = tid; i < NV; i += 256) {
+      kdst[i] = ksrc[i];
+      vdst[i] = vsrc[i];
     }
   }
   {

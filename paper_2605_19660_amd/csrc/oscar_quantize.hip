@@ -124,6 +124,19 @@ template <int STAGE> __device__ __forceinline__ float partner(float v) {
   return __builtin_bit_cast(
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
 }
+// value of lane j (a constant after unrolling) of the caller's quad
+template <int CTRL> __device__ __forceinline__ float dpp_read(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float quad_bcast(float v, int j) {
+  switch (j) {
+    case 0: return dpp_read<0x00>(v);
+    case 1: return dpp_read<0x55>(v);
+    case 2: return dpp_read<0xAA>(v);
+    default: return dpp_read<0xFF>(v);
+  }
+}
 __device__ __forceinline__ int channel_group_of_row_lane(int r) {
   const int b2 = (r >> 2) & 1;
   return ((r ^ b2) & 1) | ((((r >> 1) ^ b2) & 1) << 1) | (b2 << 2) | (r & 8);
@@ -299,7 +312,25 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   uint4 ku[8];
   Raw8<IO> vraw[8];
   float nrm[8];
-  if (do_block) {
+  if (do_block && blk * R >= sp.r0) {
+    // the whole block is new tokens (every block of a prefill): straight-line loads
+    Raw8<IO> kraw[8];
+    const size_t tok0 = (size_t)b * P.T + (size_t)(blk * R - sp.r0 + slot);
+    const IO* kp = knew + (tok0 * Hkv + kvh) * D + cg * 8;
+    const IO* vp = vnew + (tok0 * Hkv + kvh) * D + cg * 8;
+    const size_t pstride = (size_t)16 * Hkv * D;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      kraw[p].load(kp + p * pstride);
+      vraw[p].load(vp + p * pstride);
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      float x[8];
+      kraw[p].widen(x);
+      ku[p] = key_transform8<META>(x, sgn, nrm[p]);
+    }
+  } else if (do_block) {
     Raw8<IO> kraw[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
@@ -473,9 +504,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   // passes fill one byte (2-bit) / half-word (4-bit) of the piece, odd passes the other.
   {
     const int L = P.g.v_group / 8;  // lanes per value group: 4, 8 or 16
-    float wv0[8], wv1[8], zv0 = 0.0f, zv1 = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) wv0[e] = wv1[e] = 0.0f;
+    float vmn[8], vmx[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       float v[8];
@@ -486,19 +515,42 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
         mn = fminf(mn, v[e]);
         mx = fmaxf(mx, v[e]);
       }
-      if (L > 1) { mn = fminf(mn, partner<0>(mn)); mx = fmaxf(mx, partner<0>(mx)); }
-      if (L > 2) { mn = fminf(mn, partner<1>(mn)); mx = fmaxf(mx, partner<1>(mx)); }
+      mn = fminf(mn, partner<0>(mn)); mx = fmaxf(mx, partner<0>(mx));
+      mn = fminf(mn, partner<1>(mn)); mx = fmaxf(mx, partner<1>(mx));
       if (L > 4) { mn = fminf(mn, partner<2>(mn)); mx = fmaxf(mx, partner<2>(mx)); }
       if (L > 8) { mn = fminf(mn, partner<3>(mn)); mx = fmaxf(mx, partner<3>(mx)); }
-      float df, rd, z;
-      quant_params<META, BITS>(mn, mx, df, rd, z);
-      const int tok = p * 16 + slot;
-      if ((cg & (L - 1)) == 0) {
-        const int gv = cg / L;
+      vmn[p] = mn;
+      vmx[p] = mx;
+    }
+    // The 4 lanes of a quad always share a value group: lane j of the quad works out the
+    // Eq. 3-4 parameters of passes 2j and 2j+1 and the quad reads them back by broadcast.
+    const int qj = tid & 3;
+    float prd[2], plo[2], phi[2], pz[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float mn = qj == 0 ? vmn[i] : qj == 1 ? vmn[2 + i] : qj == 2 ? vmn[4 + i] : vmn[6 + i];
+      const float mx = qj == 0 ? vmx[i] : qj == 1 ? vmx[2 + i] : qj == 2 ? vmx[4 + i] : vmx[6 + i];
+      float df;
+      quant_params<META, BITS>(mn, mx, df, prd[i], pz[i]);
+      plo[i] = -pz[i];
+      phi[i] = QMAX - pz[i];
+      if ((cg & (L - 1) & ~3) == 0) {   // first quad of its value group stores the metadata
+        const int tok = (2 * qj + i) * 16 + slot, gv = cg / L;
         s_vmeta[0][gv][tok_meta_pos(tok)] = from_f32<META>(df);
-        s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(z);
+        s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(pz[i]);
       }
-      const float lo = -z, hi = QMAX - z;
+    }
+    float wv0[8], wv1[8], zv0 = 0.0f, zv1 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) wv0[e] = wv1[e] = 0.0f;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      float v[8];
+      vraw[p].widen(v);
+      const float rd = quad_bcast(prd[p & 1], p >> 1);
+      const float lo = quad_bcast(plo[p & 1], p >> 1);
+      const float hi = quad_bcast(phi[p & 1], p >> 1);
+      const float z = quad_bcast(pz[p & 1], p >> 1);
       const float pl = place_value<BITS>(p >> 1);
       if ((p & 1) == 0) {
 #pragma unroll

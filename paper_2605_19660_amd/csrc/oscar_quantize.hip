@@ -280,7 +280,8 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   __shared__ __align__(16) META s_vmeta[2][4][R];
   __shared__ __align__(16) META s_norm[R];
 
-  const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x;
+  // kv head fastest: the workgroups that share a token block's rows in memory run together
+  const int b = blockIdx.z, kvh = blockIdx.x, blk = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int slot = tid >> 4;                            // token of a pass
   const int cg = channel_group_of_row_lane(tid & 15);   // channels 8*cg .. 8*cg+7
@@ -703,7 +704,7 @@ extern "C" int oscar_quantize_append(const void* k, const void* v, int32_t T,
   P.g = make_geom(cache->cfg.bits, cache->cfg.k_group, cache->cfg.v_group, cache->cfg.meta_dtype);
   P.flags = flags;
   const int nblk = (R + T) / R;  // a sequence completes at most this many blocks
-  dim3 grid(nblk, cache->cfg.n_kv_heads, cache->batch);
+  dim3 grid(cache->cfg.n_kv_heads, nblk, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   switch (cache->cfg.io_dtype) {
     case OSCAR_F32: rc = launch_meta<float>(P, grid, st); break;

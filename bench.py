@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # each scaled by the same counter's reading for a plain 256 MiB copy kernel (summary under
 # profiles/); counters cannot be read from inside this process, so the figure is keyed by
 # the workload it was measured on and reported as null for any other.
-MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 181_313_126 + 1_114_931}
+MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 181_330_330 + 1_114_214}
 LLC_BYTES = 256 << 20       # Infinity Cache
 
 
@@ -204,6 +204,29 @@ def main():
         b_bytes = w.batch * w.n_kv_heads * w.context * 2 * w.head_dim * 2
         bf16 = {"us_per_step": b_us, "hbm_gbs": b_bytes / (b_us * 1e-6) / 1e9, "splits": bsplits}
 
+    # ---- what the same timing method shows for a pure streaming read of as many bytes ----
+    # (the uncompressed K tensor serves as the source; windows rotate so the stream is cold)
+    stream_read = None
+    src_bytes = kd.numel() * kd.element_size()
+    unit = 32768 * 512
+    probe_bytes = min(cache_bytes, src_bytes // 3) // unit * unit
+    if probe_bytes > 0:
+        n_win = max(1, min(4, src_bytes // probe_bytes))
+        kd_u8 = kd.view(torch.uint8).reshape(-1)
+        ts = []
+        for i in range(12):
+            t = ob.Timer()
+            win = kd_u8[(i % n_win) * probe_bytes:]
+            ob.probe_stream_read(win, probe_bytes, 512, timer=t, stream=stream)
+            us = t.elapsed_us()
+            t.close()
+            if i >= 4:
+                ts.append(us)
+        p_us = float(np.mean(ts))
+        stream_read = {"bytes": probe_bytes, "us": p_us, "hbm_gbs": probe_bytes / (p_us * 1e-6) / 1e9,
+                       "frac": probe_bytes / (p_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                       "what": "oscar_probe_stream_read: 512 workgroups x 256 threads, 1 KB wave loads, loads only"}
+
     res = {
         "metric": "int%d_decode_attn_us_per_step" % w.bits,
         "value": us_step, "unit": "us/step", "n_gpus": 1, "steps": args.steps,
@@ -232,6 +255,8 @@ def main():
                                     "frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                     "algorithmic_bytes": pre_bytes},
     }
+    if stream_read:
+        res["stream_read_probe"] = stream_read
     if bf16:
         res["bf16_decode"] = bf16
         res["speedup_vs_bf16_decode"] = bf16["us_per_step"] / us_step

@@ -217,6 +217,16 @@ int oscar_decode_attn_partial_timed(const void *q, const oscar_cache *cache, flo
                                     int32_t num_splits, void *workspace, size_t workspace_bytes,
                                     void *stream, oscar_timer *timer);
 
+/* Measurement aid: reads `bytes` bytes of device memory at `src` (16-byte aligned) once, with
+ * `workgroups` workgroups of 256 threads issuing wave-wide 1 KB loads, and nothing else.
+ * `bytes` must be a multiple of 32768 * workgroups (OSCAR_ERR_INVALID_ARG otherwise; nothing
+ * outside [src, src + bytes) is touched).  `sink` (device, 4 bytes, may be NULL) only keeps
+ * the loads alive.  With a timer, oscar_timer_elapsed_us gives the kernel's time: the HBM
+ * read bandwidth this timing method reports for a pure stream, next to which the decode
+ * kernel's figure can be read. */
+int oscar_probe_stream_read(const void *src, size_t bytes, int32_t workgroups, void *sink,
+                            void *stream, oscar_timer *timer);
+
 /* 16-bit comparator: the same split-K decode attention on an uncompressed,
  * un-rotated cache (the BF16 FlashDecoding-style baseline of the paper's
  * efficiency section).

@@ -26,7 +26,8 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_auto_splits", "oscar_decode_workspace_bytes", "oscar_quantize_append",
            "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
-           "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed")
+           "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
+           "oscar_probe_stream_read")
 
 
 class OscarError(RuntimeError):
@@ -93,6 +94,8 @@ def lib():
     L.oscar_timer_destroy.argtypes = [vp]
     L.oscar_timer_elapsed_us.restype = C.c_int
     L.oscar_timer_elapsed_us.argtypes = [vp, C.POINTER(C.c_float)]
+    L.oscar_probe_stream_read.restype = C.c_int
+    L.oscar_probe_stream_read.argtypes = [vp, sz, i32, vp, vp, vp]
     L.oscar_decode_attn_reduce.restype = C.c_int
     L.oscar_decode_attn_reduce.argtypes = [C.POINTER(CCache), vp, i32, i32, vp, sz, vp]
     L.oscar_bf16_decode_attn.restype = C.c_int
@@ -264,6 +267,14 @@ class Timer:
         if self.handle:
             lib().oscar_timer_destroy(self.handle)
             self.handle = C.c_void_p()
+
+
+def probe_stream_read(src, nbytes: int, workgroups: int, timer: "Timer | None" = None, stream=None):
+    """oscar_probe_stream_read: plain streaming read of the first `nbytes` bytes of tensor `src`."""
+    assert src.is_cuda and src.is_contiguous() and nbytes <= src.numel() * src.element_size()
+    rc = lib().oscar_probe_stream_read(src.data_ptr(), nbytes, workgroups, None,
+                                       _stream_ptr(stream), timer.handle if timer else None)
+    _check(rc, "oscar_probe_stream_read")
 
 
 def decode_attn_partial(cache: Cache, q, workspace, num_splits: int, scale: float = 0.0,

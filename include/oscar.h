@@ -230,16 +230,20 @@ int oscar_probe_stream_read(const void *src, size_t bytes, int32_t workgroups, v
 /* 16-bit comparator: the same split-K decode attention on an uncompressed,
  * un-rotated cache (the BF16 FlashDecoding-style baseline of the paper's
  * efficiency section).
- *   q : device [batch][n_q_heads][d]; k, v : device [batch][kv_stride_tokens][n_kv_heads][d];
+ *   q : device [batch][n_q_heads][d];
+ *   k, v : device, kv_layout OSCAR_KV_TOKEN_MAJOR: [batch][kv_stride_tokens][n_kv_heads][d],
+ *          OSCAR_KV_HEAD_MAJOR: [batch][n_kv_heads][kv_stride_tokens][d] (each kv head's tokens
+ *          contiguous, as in a paged 16-bit cache);
  *   all of `dtype` (OSCAR_BF16 or OSCAR_F16); seq_lens: device int32[batch] (<= kv_stride_tokens);
  *   out: device [batch][n_q_heads][d] of out_dtype (OSCAR_F32 or dtype);
  *   workspace as oscar_decode_workspace_bytes for the same head counts. */
+enum { OSCAR_KV_TOKEN_MAJOR = 0, OSCAR_KV_HEAD_MAJOR = 1 };
 int oscar_bf16_decode_attn(const void *q, const void *k, const void *v, const int32_t *seq_lens,
                            void *out, int32_t dtype, int32_t out_dtype, int32_t batch,
-                           int32_t kv_stride_tokens, int32_t n_q_heads, int32_t n_kv_heads,
-                           int32_t head_dim, float softmax_scale, int32_t max_seq_len_hint,
-                           int32_t num_splits, void *workspace, size_t workspace_bytes,
-                           void *stream);
+                           int32_t kv_stride_tokens, int32_t kv_layout, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                           int32_t max_seq_len_hint, int32_t num_splits, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /* Test/debug: copy sequence b, kv head h back to the HOST in a layout-free
  * form (one code per byte). Synchronizes `stream`. Host outputs, each may be

@@ -99,7 +99,7 @@ def lib():
     L.oscar_decode_attn_reduce.restype = C.c_int
     L.oscar_decode_attn_reduce.argtypes = [C.POINTER(CCache), vp, i32, i32, vp, sz, vp]
     L.oscar_bf16_decode_attn.restype = C.c_int
-    L.oscar_bf16_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+    L.oscar_bf16_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32,
                                          f32, i32, i32, vp, sz, vp]
     L.oscar_debug_dump.restype = C.c_int
     L.oscar_debug_dump.argtypes = [C.POINTER(CCache), i32, i32, i32] + [vp] * 11 + [vp]
@@ -303,11 +303,15 @@ def decode_attn_reduce(cache: Cache, out, workspace, num_splits: int, stream=Non
 
 
 def bf16_decode_attn(q, k, v, seq_lens, out=None, scale: float = 0.0, max_seq_len_hint: int = 0,
-                     num_splits: int = 0, workspace=None, stream=None):
-    """oscar_bf16_decode_attn: comparator on an uncompressed [batch, S, n_kv_heads, d] cache."""
+                     num_splits: int = 0, workspace=None, stream=None, head_major: bool = False):
+    """oscar_bf16_decode_attn: comparator on an uncompressed cache, [batch, S, n_kv_heads, d]
+    or (head_major) [batch, n_kv_heads, S, d]."""
     import torch
     assert q.is_cuda and k.is_contiguous() and v.is_contiguous() and q.is_contiguous()
-    B, S, Hkv, d = k.shape
+    if head_major:
+        B, Hkv, S, d = k.shape
+    else:
+        B, S, Hkv, d = k.shape
     Hq = q.shape[1]
     cfg = Config(Hq, Hkv, d)
     if out is None:
@@ -320,7 +324,7 @@ def bf16_decode_attn(q, k, v, seq_lens, out=None, scale: float = 0.0, max_seq_le
     rc = lib().oscar_bf16_decode_attn(q.data_ptr(), k.data_ptr(), v.data_ptr(),
                                       None if seq_lens is None else seq_lens.data_ptr(),
                                       out.data_ptr(), dtype_code(k.dtype), dtype_code(out.dtype), B,
-                                      S, Hq, Hkv, d, scale, max_seq_len_hint, num_splits,
+                                      S, 1 if head_major else 0, Hq, Hkv, d, scale, max_seq_len_hint, num_splits,
                                       workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(rc, "oscar_bf16_decode_attn")
     return out

@@ -1,6 +1,7 @@
 // 16-bit comparator: split-K decode attention softmax(q K^T) V on an uncompressed,
-// un-rotated cache [batch][tokens][kv heads][128] (the BF16 FlashDecoding-style
-// baseline of the paper's efficiency section).  Same split / partial / reduce
+// un-rotated cache, token-major [batch][tokens][kv heads][128] or head-major
+// [batch][kv heads][tokens][128] (the BF16 FlashDecoding-style baseline of the paper's
+// efficiency section).  Same split / partial / reduce
 // skeleton as the compressed path, 512 bytes per token and kv head.
 //
 // Tile = 64 tokens.  Keys go global -> LDS with 16-byte coalesced loads (padded rows),
@@ -24,6 +25,7 @@ struct PlainParams {
   const int32_t* seq_lens;
   float* ws;
   int batch, S, Hq, Hkv, num_splits;
+  int head_major;   // 0: [batch][tokens][kv heads][d], 1: [batch][kv heads][tokens][d]
   float qk_scale_log2;
 };
 
@@ -78,8 +80,10 @@ __global__ __launch_bounds__(256) void oscar_plain_decode_partial_kernel(PlainPa
 
   const uint8_t* kbase = reinterpret_cast<const uint8_t*>(P.k);
   const uint8_t* vbase = reinterpret_cast<const uint8_t*>(P.v);
-  const size_t row_stride = (size_t)P.Hkv * D * 2;  // bytes between consecutive tokens
-  const size_t seq_off = ((size_t)b * P.S * P.Hkv + kvh) * D * 2;
+  // bytes between consecutive tokens of one kv head, and offset of this stream
+  const size_t row_stride = P.head_major ? (size_t)D * 2 : (size_t)P.Hkv * D * 2;
+  const size_t seq_off = P.head_major ? ((size_t)b * P.Hkv + kvh) * P.S * D * 2
+                                      : ((size_t)b * P.S * P.Hkv + kvh) * D * 2;
 
   const int tok = tid >> 2, quarter = tid & 3;  // logits: 4 lanes per token
   const int c4 = tid & 31, tg = tid >> 5;       // values: 4 channels per lane, 8 token phases
@@ -221,7 +225,7 @@ int launch_plain(const PlainParams& P, int gq, dim3 grid, hipStream_t st) {
 extern "C" int oscar_bf16_decode_attn(const void* q, const void* k, const void* v,
                                       const int32_t* seq_lens, void* out, int32_t dtype,
                                       int32_t out_dtype, int32_t batch, int32_t kv_stride_tokens,
-                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                      int32_t kv_layout, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                       float softmax_scale, int32_t max_seq_len_hint,
                                       int32_t num_splits, void* workspace, size_t workspace_bytes,
                                       void* stream) {
@@ -229,6 +233,7 @@ extern "C" int oscar_bf16_decode_attn(const void* q, const void* k, const void* 
   if (batch <= 0 || kv_stride_tokens <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 ||
       n_q_heads % n_kv_heads != 0 || num_splits < 0 || num_splits > 512 || max_seq_len_hint < 0)
     return OSCAR_ERR_INVALID_ARG;
+  if (kv_layout != OSCAR_KV_TOKEN_MAJOR && kv_layout != OSCAR_KV_HEAD_MAJOR) return OSCAR_ERR_INVALID_ARG;
   if (dtype != OSCAR_BF16 && dtype != OSCAR_F16) return OSCAR_ERR_UNSUPPORTED;
   if (out_dtype != OSCAR_F32 && out_dtype != dtype) return OSCAR_ERR_INVALID_ARG;
   if (head_dim != OSCAR_D || n_q_heads / n_kv_heads > OSCAR_MAX_GQA) return OSCAR_ERR_UNSUPPORTED;
@@ -248,6 +253,7 @@ extern "C" int oscar_bf16_decode_attn(const void* q, const void* k, const void* 
   P.ws = reinterpret_cast<float*>(workspace);
   P.batch = batch; P.S = kv_stride_tokens; P.Hq = n_q_heads; P.Hkv = n_kv_heads;
   P.num_splits = num_splits;
+  P.head_major = (kv_layout == OSCAR_KV_HEAD_MAJOR) ? 1 : 0;
   const float scale = softmax_scale > 0.0f ? softmax_scale : 0.08838834764831845f;
   P.qk_scale_log2 = scale * 1.4426950408889634f;
   dim3 grid(num_splits, n_kv_heads, batch);

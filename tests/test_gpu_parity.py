@@ -280,6 +280,12 @@ def test_bf16_comparator_matches_plain_attention_oracle(io):
         out = ob.bf16_decode_attn(to_dev(q, io), to_dev(k, io), to_dev(v, io),
                                   torch.from_numpy(lens).cuda(), num_splits=splits).cpu().numpy()
         assert_decode_close(out, want)
+        # same cache with each kv head's tokens contiguous
+        kh = to_dev(k, io).permute(0, 2, 1, 3).contiguous()
+        vh = to_dev(v, io).permute(0, 2, 1, 3).contiguous()
+        out = ob.bf16_decode_attn(to_dev(q, io), kh, vh, torch.from_numpy(lens).cuda(),
+                                  num_splits=splits, head_major=True).cpu().numpy()
+        assert_decode_close(out, want)
 
 
 # ------------------------------------------------- full size, sampled check --

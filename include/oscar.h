@@ -65,7 +65,7 @@ enum {
 /* Parameters of the method (Algorithm "The OScaR algorithm": G, R, d_h; Eq. 3-4: b).
  * Checked on every call. Built: head_dim 128; bits 2|4; k_group 32|64|128;
  * v_group 32|64|128; page_size 128; io_dtype any; meta_dtype F16|F32;
- * zp_mode OSCAR_ZP_INT; norm_scope OSCAR_NORM_PER_HEAD; n_q_heads/n_kv_heads <= 8.
+ * zp_mode OSCAR_ZP_INT|OSCAR_ZP_MIN; norm_scope OSCAR_NORM_PER_HEAD; n_q_heads/n_kv_heads <= 8.
  * Anything else returns OSCAR_ERR_UNSUPPORTED. */
 typedef struct oscar_config {
   int32_t head_dim;    /* d_h */

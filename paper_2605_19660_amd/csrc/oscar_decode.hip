@@ -7,7 +7,8 @@
 // "The OScaR algorithm", lines K_all / V_all / Attention; quantizer of Eq. 3-4.)
 //
 // The scales are folded so the inner loops touch raw integer codes:
-//   A[g][h][j] = Q_h[h][j] * Delta_k[g][j]   and   bias[g][h] = sum_j A[g][h][j] * z_k[g][j]
+//   A[g][h][j] = Q_h[h][j] * Delta_k[g][j]   and   bias[g][h] = sum_j Q_h[h][j] * (Delta_k z_k)[g][j]
+//   (float zero-point mode: bias = -sum_j Q_h[h][j] * zero_k[g][j])
 // are built once per page, so logit = n_i * (sum_j A * c - bias); on the value side
 // w = Delta_v * c + (-Delta_v * z_v) is one fused multiply-add per element.
 // One workgroup serves all query heads of a kv head, so every packed byte is read once.
@@ -35,6 +36,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
   const int ngk = P.g.ngk, ngv = P.g.ngv, mb = P.g.meta_bytes;
+  const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
 
   const int seq_len = P.c.seq_lens[b];
   const int r = P.c.res_lens[b];
@@ -94,15 +96,19 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
     // (0) metadata -> LDS as fp32, un-permuted (keys by channel, tokens in chunk order)
     for (int i = tid; i < ngk * D; i += 256) {
       const int gk = i / D, pos = kmeta_pos_of_chan(BITS, i % D);
-      s_kd[gk][i % D] = load_meta(kmeta, (size_t)gk * D + pos, mb);
-      s_kz[gk][i % D] = load_meta(kmeta, (size_t)(ngk + gk) * D + pos, mb);
+      const float dk = load_meta(kmeta, (size_t)gk * D + pos, mb);
+      const float zk = load_meta(kmeta, (size_t)(ngk + gk) * D + pos, mb);
+      s_kd[gk][i % D] = dk;
+      // what one unit of Q_h on this channel takes off the logit: Delta*z (integer zero-point)
+      // or -zero (float zero-point: x = Delta*c + zero)
+      s_kz[gk][i % D] = zp_min ? -zk : dk * zk;
     }
     if (tid < R) s_norm[tid] = load_meta(knorm, tok_meta_pos(tid), mb);
     for (int i = tid; i < ngv * R; i += 256) {
       const int gv = i / R, t = i % R;
       const float dv = load_meta(vmeta, (size_t)gv * R + tok_meta_pos(t), mb);
       const float zv = load_meta(vmeta, (size_t)(ngv + gv) * R + tok_meta_pos(t), mb);
-      s_vdz[gv][chunk_order(BITS, t)] = make_float2(dv, -dv * zv);
+      s_vdz[gv][chunk_order(BITS, t)] = make_float2(dv, zp_min ? zv : -dv * zv);
     }
     __syncthreads();
     // (1) A = Q_h * Delta_k, bias = sum_j A * z_k ; pair (group, head) -> one wave
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
       const float a1 = s_q[h][lane + 64] * s_kd[gk][lane + 64];
       s_A[gk][h][lane] = a0;
       s_A[gk][h][lane + 64] = a1;
-      const float part = wave_sum(a0 * s_kz[gk][lane] + a1 * s_kz[gk][lane + 64]);
+      const float part = wave_sum(s_q[h][lane] * s_kz[gk][lane] + s_q[h][lane + 64] * s_kz[gk][lane + 64]);
       if (lane == 0) s_bias[gk][h] = part;
     }
     __syncthreads();

@@ -139,6 +139,15 @@ __device__ __forceinline__ void mix_mul_pair(uint32_t a, uint32_t b, float& lo, 
   asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,1,0]" : "=v"(lo) : "v"(a), "v"(b));
   asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(hi) : "v"(a), "v"(b));
 }
+// -(fp16 value), widened: the zero-point term of the float zero-point mode
+__device__ __forceinline__ void neg_widen8(const uint4& a, float (&x)[8]) {
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = -__half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
+    x[2 * i + 1] = -__half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+  }
+}
 __device__ __forceinline__ void mix_mul8(const uint4& a, const uint4& b, float (&x)[8]) {
   mix_mul_pair(a.x, b.x, x[0], x[1]);
   mix_mul_pair(a.y, b.y, x[2], x[3]);
@@ -383,6 +392,7 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, q4 = lane >> 4;
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
+  const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
 
   // Pages are dealt round-robin: wave w of split s owns pages 4*s + w + 4*S*k.  The page
   // numbers (and so the block-table addresses) do not depend on the sequence length, which
@@ -619,8 +629,11 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
       const uint32_t nt[4] = {kr.nr.x, kr.nr.y, kr.nr.z, kr.nr.w};
 #pragma unroll
       for (int g = 0; g < NGK; ++g) {
+        // per channel, what one unit of Q_h takes off the logit: Delta*z, or -zero when the
+        // zero-point is the float group minimum (x = Delta*c + zero)
         float dz[8];
-        mix_mul8(kr.kd[g], kr.kz[g], dz);
+        if (zp_min) neg_widen8(kr.kz[g], dz);
+        else mix_mul8(kr.kd[g], kr.kz[g], dz);
         float bias[HP];
 #pragma unroll
         for (int s = 0; s < HP; ++s) {
@@ -731,7 +744,8 @@ __global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams 
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
       float dz[8];
-      mix_mul8(vr.vd[g], vr.vz[g], dz);
+      if (zp_min) neg_widen8(vr.vz[g], dz);
+      else mix_mul8(vr.vd[g], vr.vz[g], dz);
       vr.load_zero(nx, g, lane);
 #pragma unroll
       for (int s = 0; s < HP; ++s) {

@@ -194,8 +194,11 @@ __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&
 }
 
 // Eq. 3-4 parameters of one group, rounded to storage before use.
+// zp_min: the zero-point is the group minimum itself (float zero-point form of the complexity
+// appendix) instead of the integer of Eq. 3-4.
 template <typename META, int BITS>
-__device__ __forceinline__ void quant_params(float mn, float mx, float& df, float& rd, float& z) {
+__device__ __forceinline__ void quant_params(float mn, float mx, bool zp_min, float& df, float& rd,
+                                             float& z) {
   const float qmax = (float)((1 << BITS) - 1);
   float dl = (mx - mn) / qmax;
   df = round_meta<META>(dl);
@@ -204,7 +207,7 @@ __device__ __forceinline__ void quant_params(float mn, float mx, float& df, floa
     if (df == 0.0f || isinf(df)) df = 1.0f;
   }
   rd = 1.0f / df;
-  z = round_meta<META>(rintf(-mn * rd));
+  z = zp_min ? round_meta<META>(mn) : round_meta<META>(rintf(-mn * rd));
 }
 
 // packed fp16 min / max (finite inputs); volatile: plain asm blocks of this kind have been
@@ -223,9 +226,13 @@ __device__ __forceinline__ float half_of(uint32_t w, int hi) {
   return __half2float(__ushort_as_half((unsigned short)(hi ? (w >> 16) : (w & 0xffffu))));
 }
 
-// clamp(rint(x * rd) + z, 0, qmax) - z, i.e. the code minus its zero-point (an integer in
-// fp32): lo = -z, hi = qmax - z.
-__device__ __forceinline__ float code_minus_zero(float x, float rd, float lo, float hi) {
+// Integer zero-point: clamp(rint(x * rd) + z, 0, qmax) - z, i.e. the code minus its
+// zero-point (an integer in fp32), with lo = -z, hi = qmax - z.
+// Float zero-point (ZPMIN): the code itself, clamp(rint((x - zero) * rd), 0, qmax), with
+// lo = zero and hi unused.
+template <bool ZPMIN, int BITS>
+__device__ __forceinline__ float code_term(float x, float rd, float lo, float hi) {
+  if (ZPMIN) return __builtin_amdgcn_fmed3f(rintf((x - lo) * rd), 0.0f, (float)((1 << BITS) - 1));
   return __builtin_amdgcn_fmed3f(rintf(x * rd), lo, hi);
 }
 
@@ -263,6 +270,33 @@ template <int BITS> __device__ __forceinline__ constexpr float place_value(int i
   return v;
 }
 
+// One token's 8 codes of a channel group -> one 16-bit (2-bit codes) or 32-bit (4-bit codes)
+// piece of chunk (tile = tok/16, n = tok%16, q4 = cg/4) of the key-code page image.
+template <bool ZPMIN, int BITS>
+__device__ __forceinline__ void key_codes(const uint4& ku, const float (&rd)[8], const float (&lo)[8],
+                                          const float (&hi)[8], float zs0, float zs1,
+                                          uint8_t* s_kimg, int tok, int cg) {
+  float x[8];
+  widen_halves(ku, x);
+  const int off = chunk_offset(BITS, tok / 16, tok % 16, cg / 4) + (cg % 4) * BITS;
+  if (BITS == 2) {
+    float w = zs0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      w = fmaf(code_term<ZPMIN, BITS>(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w);
+    *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)(uint32_t)w;
+  } else {
+    float w0 = zs0, w1 = zs1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w0 = fmaf(code_term<ZPMIN, BITS>(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w0);
+      w1 = fmaf(code_term<ZPMIN, BITS>(x[e + 4], rd[e + 4], lo[e + 4], hi[e + 4]),
+                place_value<BITS>(e), w1);
+    }
+    *reinterpret_cast<uint32_t*>(&s_kimg[off]) = (uint32_t)w0 | ((uint32_t)w1 << 16);
+  }
+}
+
 template <typename IO, typename META, int BITS, int KG>
 __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   constexpr int NGK = R / KG;        // key groups per page
@@ -286,6 +320,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   const int slot = tid >> 4;                            // token of a pass
   const int cg = channel_group_of_row_lane(tid & 15);   // channels 8*cg .. 8*cg+7
   const int Hkv = P.c.cfg.n_kv_heads;
+  const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
   uint32_t sgn[4];
 #pragma unroll
   for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
@@ -450,10 +485,11 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
         mxw = w == 0 ? bb : pk_max_f16(mxw, bb);
       }
       float df, rd, z;
-      quant_params<META, BITS>(half_of(mnw, e & 1), half_of(mxw, e & 1), df, rd, z);
+      quant_params<META, BITS>(half_of(mnw, e & 1), half_of(mxw, e & 1), zp_min, df, rd, z);
       // place value of this channel's code inside its packed word (4-bit: two 16-bit halves)
       const float place = ldexpf(1.0f, BITS * ((BITS == 2) ? e : (e & 3)));
-      s_par[gk][c] = make_float4(rd, -z, QMAX - z, z * place);
+      s_par[gk][c] = zp_min ? make_float4(rd, z, 0.0f, 0.0f)
+                            : make_float4(rd, -z, QMAX - z, z * place);
       const int pos = kmeta_pos_of_chan(BITS, c);
       o_kmeta[(size_t)gk * D + pos] = from_f32<META>(df);
       o_kmeta[(size_t)(NGK + gk) * D + pos] = from_f32<META>(z);
@@ -475,27 +511,14 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       if (BITS == 2 || e < 4) zs0 += q.w;
       else zs1 += q.w;
     }
+    if (zp_min) {
 #pragma unroll
-    for (int p = gk * PPG; p < (gk + 1) * PPG; ++p) {
-      float x[8];
-      widen_halves(ku[p], x);
-      const int tok = p * 16 + slot;
-      const int off = chunk_offset(BITS, tok / 16, tok % 16, cg / 4) + (cg % 4) * BITS;
-      if (BITS == 2) {
-        float w = zs0;
+      for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
+        key_codes<true, BITS>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
+    } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-          w = fmaf(code_minus_zero(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w);
-        *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)(uint32_t)w;
-      } else {
-        float w0 = zs0, w1 = zs1;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          w0 = fmaf(code_minus_zero(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w0);
-          w1 = fmaf(code_minus_zero(x[e + 4], rd[e + 4], lo[e + 4], hi[e + 4]), place_value<BITS>(e), w1);
-        }
-        *reinterpret_cast<uint32_t*>(&s_kimg[off]) = (uint32_t)w0 | ((uint32_t)w1 << 16);
-      }
+      for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
+        key_codes<false, BITS>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
     }
   }
 
@@ -532,8 +555,8 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       const float mn = qj == 0 ? vmn[i] : qj == 1 ? vmn[2 + i] : qj == 2 ? vmn[4 + i] : vmn[6 + i];
       const float mx = qj == 0 ? vmx[i] : qj == 1 ? vmx[2 + i] : qj == 2 ? vmx[4 + i] : vmx[6 + i];
       float df;
-      quant_params<META, BITS>(mn, mx, df, prd[i], pz[i]);
-      plo[i] = -pz[i];
+      quant_params<META, BITS>(mn, mx, zp_min, df, prd[i], pz[i]);
+      plo[i] = zp_min ? pz[i] : -pz[i];
       phi[i] = QMAX - pz[i];
       if ((cg & (L - 1) & ~3) == 0) {   // first quad of its value group stores the metadata
         const int tok = (2 * qj + i) * 16 + slot, gv = cg / L;
@@ -551,15 +574,23 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       const float rd = quad_bcast(prd[p & 1], p >> 1);
       const float lo = quad_bcast(plo[p & 1], p >> 1);
       const float hi = quad_bcast(phi[p & 1], p >> 1);
-      const float z = quad_bcast(pz[p & 1], p >> 1);
+      const float z = zp_min ? 0.0f : quad_bcast(pz[p & 1], p >> 1);
       const float pl = place_value<BITS>(p >> 1);
+      float t[8];
+      if (zp_min) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = code_term<true, BITS>(v[e], rd, lo, hi);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = code_term<false, BITS>(v[e], rd, lo, hi);
+      }
       if ((p & 1) == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) wv0[e] = fmaf(code_minus_zero(v[e], rd, lo, hi), pl, wv0[e]);
+        for (int e = 0; e < 8; ++e) wv0[e] = fmaf(t[e], pl, wv0[e]);
         zv0 = fmaf(z, pl, zv0);
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) wv1[e] = fmaf(code_minus_zero(v[e], rd, lo, hi), pl, wv1[e]);
+        for (int e = 0; e < 8; ++e) wv1[e] = fmaf(t[e], pl, wv1[e]);
         zv1 = fmaf(z, pl, zv1);
       }
     }

@@ -46,10 +46,10 @@ def test_cache_sizes_match_the_format():
 @pytest.mark.parametrize("kw,code", [
     (dict(head_dim=64), ob.ERR_UNSUPPORTED),
     (dict(bits=3), ob.ERR_UNSUPPORTED),
+    (dict(zp_mode=7), ob.ERR_INVALID_ARG),
     (dict(bits=0), ob.ERR_INVALID_ARG),
     (dict(k_group=48), ob.ERR_INVALID_ARG),
     (dict(k_group=16), ob.ERR_UNSUPPORTED),
-    (dict(zp_mode=ob.ZP_MIN), ob.ERR_UNSUPPORTED),
     (dict(norm_scope=ob.NORM_ALL_KV_HEADS), ob.ERR_UNSUPPORTED),
     (dict(n_q_heads=30), ob.ERR_INVALID_ARG),
     (dict(n_q_heads=128), ob.ERR_UNSUPPORTED),

@@ -33,13 +33,14 @@ def to_dev(x, io):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dt).contiguous()
 
 
-def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True):
+def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True, zp_mode=0):
     ob = _ob()
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
-                    w.page_size, DT[w.io_dtype], DT[w.meta_dtype])
+                    w.page_size, DT[w.io_dtype], DT[w.meta_dtype], zp_mode=zp_mode)
     g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm, fused=fused)
     o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
-                                 DT[w.meta_dtype]), w.batch, w.n_kv_heads, (cap_pages + 1) * w.page_size)
+                                 DT[w.meta_dtype], zp_mode=zp_mode), w.batch, w.n_kv_heads,
+                    (cap_pages + 1) * w.page_size)
     return g, o
 
 
@@ -263,6 +264,36 @@ def test_decode_paths_and_fusion_agree_with_oracle(monkeypatch, path, fused, hq,
             assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
     torch.cuda.synchronize()
     assert int(g.tickets.abs().sum().item()) == 0       # every ticket handed back
+
+
+# ------------------------------------------------ float zero-point variant --
+
+@pytest.mark.parametrize("io,meta,bits,kg,vg,path", [
+    ("bf16", "f16", 2, 128, 32, "mfma"),
+    ("bf16", "f16", 4, 32, 32, "mfma"),
+    ("f16", "f16", 2, 128, 128, "generic"),
+    ("f32", "f32", 4, 64, 64, "mfma"),      # fp32 metadata: the generic kernel either way
+])
+def test_float_zero_point_mode_bitexact_and_decode(io, meta, bits, kg, vg, path, monkeypatch):
+    """zp_mode = ZP_MIN (zero-point = the group minimum, x = Delta*c + zero): encoder bit-exact,
+    token-by-token appends included, and both decode kernels within tolerance."""
+    ob = _ob()
+    if path == "generic":
+        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 3 + 61,
+                                  io_dtype=io, meta_dtype=meta, bits=bits, k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8, zp_mode=ob.ZP_MIN)
+    n0 = 128 * 2 + 17
+    ob.quantize_append(g, to_dev(k[:, :n0], io), to_dev(v[:, :n0], io), eager=True, max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    for t in range(n0, w.context):      # crosses a page boundary: one deferred flush
+        ob.quantize_append(g, to_dev(k[:, t:t + 1], io), to_dev(v[:, t:t + 1], io))
+        o.append(k[:, t:t + 1], v[:, t:t + 1])
+    assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
 
 
 # -------------------------------------------------------------- comparator --

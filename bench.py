@@ -11,7 +11,12 @@ timed region.  To keep the numbers HBM numbers and not Infinity-Cache numbers th
 rotate over several independent cache copies (think: layers) whose total footprint exceeds
 twice the 256 MB last-level cache.
 
-Prints ONE JSON line (see the design doc for the field definitions).
+Prints ONE JSON line: metric / value / unit / step counts / config, plus
+  roofline           the split-K partial kernel: algorithmic bytes per launch over its mean device
+                     time (HIP events attached to the dispatch), against 8 TB/s; `traffic` = HBM
+                     bytes per launch from FETCH_SIZE / WRITE_SIZE counter runs,
+  stream_read_probe  the same timing method on a loads-only kernel of the same launch shape,
+  quantize_append_prefill, bf16_decode (the 16-bit comparator), cpu_baseline (the CPU oracle).
 """
 from __future__ import annotations
 

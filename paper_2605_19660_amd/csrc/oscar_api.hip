@@ -92,9 +92,11 @@ extern "C" int32_t oscar_decode_auto_splits(const oscar_config* cfg, int32_t bat
     n_cu = prop.multiProcessorCount;
   const int pages = max_seq_len > 0 ? (max_seq_len + OSCAR_R - 1) / OSCAR_R : 1;
   const int units = batch * cfg->n_kv_heads;
-  // two workgroups (8 waves) per CU are resident at a time and every wave wants at least
-  // two pages: aim at one round of workgroups
-  int splits = (2 * n_cu) / units;
+  // two workgroups (8 waves) per CU are resident at a time (one when more than 4 query heads
+  // share a kv head: that kernel variant needs the whole register file) and every wave wants
+  // at least two pages: aim at one round of workgroups
+  const int gq = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 1;
+  int splits = ((gq > 4 ? 1 : 2) * n_cu) / units;
   const int max_by_pages = pages / 8 > 0 ? pages / 8 : 1;
   if (splits > max_by_pages) splits = max_by_pages;
   if (splits < 1) splits = 1;

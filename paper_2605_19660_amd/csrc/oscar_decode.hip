@@ -312,6 +312,35 @@ __global__ __launch_bounds__(128) void oscar_decode_reduce_kernel(const float* w
   const size_t unit = (size_t)blockIdx.y * gridDim.x + blockIdx.x;  // b * Hq + h
   const int c = threadIdx.x;
   const float* rec = ws + unit * num_splits * WS_STRIDE;
+  if (num_splits <= 16) {
+    // few splits: every thread fetches all the split statistics (same addresses across the
+    // wave) together with its own channel of every partial output, one round of loads and
+    // no barrier
+    float m[16], l[16], o[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const bool on = s < num_splits;
+      m[s] = on ? rec[(size_t)s * WS_STRIDE + D] : -INFINITY;
+      l[s] = on ? rec[(size_t)s * WS_STRIDE + D + 1] : 0.0f;
+      o[s] = on ? rec[(size_t)s * WS_STRIDE + c] : 0.0f;
+    }
+    float M = m[0];
+#pragma unroll
+    for (int s = 1; s < 16; ++s) M = fmaxf(M, m[s]);
+    float L = 0.0f, acc = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const float w = (m[s] == -INFINITY) ? 0.0f : exp2f(m[s] - M);
+      L = fmaf(l[s], w, L);
+      acc = fmaf(o[s], w, acc);
+    }
+    const float res = L > 0.0f ? acc / L : 0.0f;
+    const size_t oi = unit * D + c;
+    if (out_dtype == OSCAR_F32) reinterpret_cast<float*>(out)[oi] = res;
+    else if (out_dtype == OSCAR_BF16) reinterpret_cast<__hip_bfloat16*>(out)[oi] = __float2bfloat16(res);
+    else reinterpret_cast<__half*>(out)[oi] = __float2half_rn(res);
+    return;
+  }
   // pass 1: M
   float mloc = -INFINITY;
   for (int s = c; s < num_splits; s += 128) mloc = fmaxf(mloc, rec[(size_t)s * WS_STRIDE + D]);

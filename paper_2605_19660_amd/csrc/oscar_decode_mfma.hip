@@ -373,8 +373,11 @@ __device__ __forceinline__ float max8_halves(const uint4& r) {
 // accumulator lane group q4 (rows 4*q4..4*q4+3) owns heads q4 (slot 0) and q4+4 (slot 1).
 __device__ __forceinline__ int row_hi(int h) { return 4 * (h & 3) + 2 * (h >> 2); }
 
+// HP = head slots per accumulator lane group: 1 for up to 4 query heads per kv head (two
+// workgroups per CU), 2 for 5..8 (twice the per-head registers: one workgroup per CU, the
+// overflow lives in accumulation registers instead of scratch memory).
 template <int BITS, int HP, int NGK, int NGV>
-__global__ __launch_bounds__(256, 2) void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
+__global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   constexpr int TPG = 8 / NGK;  // token tiles per key group
   constexpr int CPG = 8 / NGV;  // channel tiles per value group
   constexpr int TABW = D + 8;   // operand table row stride in halves

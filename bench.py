@@ -248,6 +248,26 @@ def main():
                        "frac": probe_bytes / (p_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                        "what": "oscar_probe_stream_read: 512 workgroups x 256 threads, 1 KB wave loads, loads only"}
 
+    # ---- stand-alone rotation + token scaling of all keys (kernel (i) on its own) ----
+    rot = None
+    if w.meta_dtype == "f16":
+        ts = []
+        for i in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            ku, kn = ob.rotate(kd, normalize=True, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if i:
+                ts.append(e0.elapsed_time(e1) * 1e3)
+            del ku, kn
+        r_us = float(np.median(ts))
+        r_bytes = pre_units * (w.head_dim * el + w.head_dim * 2 + 2)
+        rot = {"vectors": pre_units, "us": r_us, "hbm_gbs": r_bytes / (r_us * 1e-6) / 1e9,
+               "frac": r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": r_bytes,
+               "what": "oscar_rotate(NORMALIZE) on every key vector: read input, write fp16 K_u + norm "
+                       "(includes the output allocation of the binding)"}
+
     res = {
         "metric": "int%d_decode_attn_us_per_step" % w.bits,
         "value": us_step, "unit": "us/step", "n_gpus": 1, "steps": args.steps,
@@ -276,6 +296,8 @@ def main():
                                     "frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                     "algorithmic_bytes": pre_bytes},
     }
+    if rot:
+        res["rotate_keys"] = rot
     if stream_read:
         res["stream_read_probe"] = stream_read
     if bf16:

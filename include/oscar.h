@@ -202,6 +202,25 @@ int oscar_decode_attn_reduce(const oscar_cache *cache, void *out, int32_t out_dt
                              int32_t num_splits, const void *workspace, size_t workspace_bytes,
                              void *stream);
 
+/* Stand-alone Canalized Rotation, with or without Omni-Token Scaling (kernel (i) of Sec.
+ * "Efficient System Design"; App. "Implementation Details", "Overall Design"), on n_vec
+ * vectors of 128 channels, x: device [n_vec][128] of io_dtype.
+ *   flags = 0                      : out = H(x)/sqrt(128), device [n_vec][128] fp32 (queries);
+ *                                    norms ignored
+ *   OSCAR_ROTATE_NORMALIZE         : norms[v] = ||H(x_v)/sqrt(128)||_2 rounded to meta_dtype
+ *                                    (F16|F32), out = fp16 [n_vec][128] of the quotient by the
+ *                                    stored norm: exactly what oscar_quantize_append keeps in the
+ *                                    residual window
+ *   ... | OSCAR_ROTATE_FAST_RSQRT  : the norm through the hardware reciprocal square root
+ *                                    (the paper's fast variant) instead of sqrt and divide;
+ *                                    results agree with the exact mode to about one fp16 ulp
+ *                                    and are not bit-reproducible on a CPU
+ * Returns OSCAR_ERR_INVALID_ARG for NULL pointers, unknown flags, or FAST_RSQRT without
+ * NORMALIZE. */
+enum { OSCAR_ROTATE_NORMALIZE = 1u, OSCAR_ROTATE_FAST_RSQRT = 2u };
+int oscar_rotate(const void *x, void *out, void *norms, int64_t n_vec, int32_t io_dtype,
+                 int32_t meta_dtype, uint32_t flags, void *stream);
+
 /* Measurement aid (not part of the method): a timer owns a pair of HIP events.
  * oscar_decode_attn_partial_timed is oscar_decode_attn_partial with the events attached to
  * the kernel's own dispatch (start/stop events of an extended launch), so that

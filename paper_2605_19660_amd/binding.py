@@ -27,7 +27,7 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
-           "oscar_probe_stream_read")
+           "oscar_probe_stream_read", "oscar_rotate")
 
 
 class OscarError(RuntimeError):
@@ -94,6 +94,8 @@ def lib():
     L.oscar_timer_destroy.argtypes = [vp]
     L.oscar_timer_elapsed_us.restype = C.c_int
     L.oscar_timer_elapsed_us.argtypes = [vp, C.POINTER(C.c_float)]
+    L.oscar_rotate.restype = C.c_int
+    L.oscar_rotate.argtypes = [vp, vp, vp, C.c_int64, i32, i32, C.c_uint32, vp]
     L.oscar_probe_stream_read.restype = C.c_int
     L.oscar_probe_stream_read.argtypes = [vp, sz, i32, vp, vp, vp]
     L.oscar_decode_attn_reduce.restype = C.c_int
@@ -267,6 +269,28 @@ class Timer:
         if self.handle:
             lib().oscar_timer_destroy(self.handle)
             self.handle = C.c_void_p()
+
+
+ROTATE_NORMALIZE, ROTATE_FAST_RSQRT = 1, 2
+
+
+def rotate(x, normalize: bool = False, fast_rsqrt: bool = False, meta_dtype: int = F16, stream=None):
+    """oscar_rotate on a [..., 128] tensor: H(x)/sqrt(128) as fp32, or (normalize) the fp16
+    unit-norm rotated vectors and their norms."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.shape[-1] == 128
+    n_vec = x.numel() // 128
+    if normalize:
+        out = torch.empty(x.shape, dtype=torch.float16, device=x.device)
+        norms = torch.empty(x.shape[:-1], dtype=torch_dtype(meta_dtype), device=x.device)
+    else:
+        out = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+        norms = None
+    flags = (ROTATE_NORMALIZE if normalize else 0) | (ROTATE_FAST_RSQRT if fast_rsqrt else 0)
+    rc = lib().oscar_rotate(x.data_ptr(), out.data_ptr(), None if norms is None else norms.data_ptr(),
+                            n_vec, dtype_code(x.dtype), meta_dtype, flags, _stream_ptr(stream))
+    _check(rc, "oscar_rotate")
+    return (out, norms) if normalize else out
 
 
 def probe_stream_read(src, nbytes: int, workgroups: int, timer: "Timer | None" = None, stream=None):

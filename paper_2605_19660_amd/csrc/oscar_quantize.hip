@@ -147,9 +147,8 @@ __device__ __forceinline__ int channel_group_of_row_lane(int r) {
 // rounded to fp16 (returned packed).  Butterfly stage h pairs (i, i|h): lower <- a+b,
 // upper <- a-b; across lanes that is partner + own, with the own value negated in the
 // upper lane (sgn[stage] = sign bit there, 0 in the lower lane).
-template <typename META>
-__device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&sgn)[4],
-                                                float& n_st) {
+// H(x)/sqrt(128) of the 8 channels a lane holds (128 channels over the 16 lanes of a row).
+__device__ __forceinline__ void rotate8(float (&x)[8], const uint32_t (&sgn)[4]) {
 #pragma unroll
   for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
@@ -170,18 +169,28 @@ __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&
 #pragma unroll
   for (int i = 0; i < 8; ++i) x[i] = partner<3>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[3]);
   const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = x[i] * c;
+}
+
+// sum of squares of the 128 rotated channels: balanced tree, adjacent pairs first
+__device__ __forceinline__ float row_sumsq(const float (&x)[8]) {
   float t[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    x[i] = x[i] * c;
-    t[i] = x[i] * x[i];
-  }
-  // balanced tree, adjacent pairs first
+  for (int i = 0; i < 8; ++i) t[i] = x[i] * x[i];
   float s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
   s = s + partner<0>(s);
   s = s + partner<1>(s);
   s = s + partner<2>(s);
   s = s + partner<3>(s);
+  return s;
+}
+
+template <typename META>
+__device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&sgn)[4],
+                                                float& n_st) {
+  rotate8(x, sgn);
+  const float s = row_sumsq(x);
   float n = sqrtf(s);
   float nf = round_meta<META>(n);
   float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
@@ -704,7 +713,97 @@ int launch_meta(const AppendParams& P, dim3 grid, hipStream_t st) {
   return rc;
 }
 
+// Stand-alone rotation kernel: 16 vectors of 128 channels per workgroup (one DPP row each).
+// NORMALIZE = false: out = H(x)/sqrt(128) in fp32 (queries).
+// NORMALIZE = true : norms = ||H(x)/sqrt(128)|| (metadata type), out = fp16 of the quotient
+// (keys); `fast` takes the reciprocal square root instruction instead of sqrt + divide.
+template <typename IO, typename META, bool NORMALIZE>
+__global__ __launch_bounds__(256) void oscar_rotate_kernel(const IO* __restrict__ x, void* out,
+                                                           META* norms, long long n_vec, int fast) {
+  const int tid = threadIdx.x;
+  const int cg = channel_group_of_row_lane(tid & 15);
+  uint32_t sgn[4];
+#pragma unroll
+  for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
+  const long long v = (long long)blockIdx.x * 16 + (tid >> 4);
+  const long long vc = v < n_vec ? v : n_vec - 1;   // whole rows stay active for the exchanges
+  Raw8<IO> raw;
+  raw.load(x + (size_t)vc * D + cg * 8);
+  float xs[8];
+  raw.widen(xs);
+  if (!NORMALIZE) {
+    rotate8(xs, sgn);
+    if (v < n_vec) {
+      float4* o = reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + (size_t)v * D + cg * 8);
+      o[0] = make_float4(xs[0], xs[1], xs[2], xs[3]);
+      o[1] = make_float4(xs[4], xs[5], xs[6], xs[7]);
+    }
+    return;
+  }
+  uint4 u;
+  float nf;
+  if (fast) {
+    rotate8(xs, sgn);
+    const float s = row_sumsq(xs);
+    const float inv = s > 0.0f ? __builtin_amdgcn_rsqf(s) : 0.0f;
+    nf = round_meta<META>(s * inv);
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = half_bits(pin_f32(xs[2 * i] * inv)) | (half_bits(pin_f32(xs[2 * i + 1] * inv)) << 16);
+    u = make_uint4(w[0], w[1], w[2], w[3]);
+  } else {
+    u = key_transform8<META>(xs, sgn, nf);
+  }
+  if (v < n_vec) {
+    *reinterpret_cast<uint4*>(reinterpret_cast<__half*>(out) + (size_t)v * D + cg * 8) = u;
+    if (cg == 0) norms[v] = from_f32<META>(nf);
+  }
+}
+
+template <typename IO>
+int launch_rotate(const void* x, void* out, void* norms, long long n_vec, int meta_dtype,
+                  uint32_t flags, hipStream_t st) {
+  const dim3 grid((unsigned)((n_vec + 15) / 16));
+  const IO* xp = reinterpret_cast<const IO*>(x);
+  const int fast = (flags & OSCAR_ROTATE_FAST_RSQRT) ? 1 : 0;
+  if (!(flags & OSCAR_ROTATE_NORMALIZE)) {
+    hipLaunchKernelGGL((oscar_rotate_kernel<IO, float, false>), grid, dim3(256), 0, st, xp, out,
+                       (float*)nullptr, n_vec, 0);
+  } else if (meta_dtype == OSCAR_F16) {
+    hipLaunchKernelGGL((oscar_rotate_kernel<IO, __half, true>), grid, dim3(256), 0, st, xp, out,
+                       reinterpret_cast<__half*>(norms), n_vec, fast);
+  } else if (meta_dtype == OSCAR_F32) {
+    hipLaunchKernelGGL((oscar_rotate_kernel<IO, float, true>), grid, dim3(256), 0, st, xp, out,
+                       reinterpret_cast<float*>(norms), n_vec, fast);
+  } else {
+    return OSCAR_ERR_UNSUPPORTED;
+  }
+  return OSCAR_OK;
+}
+
 }  // namespace
+
+extern "C" int oscar_rotate(const void* x, void* out, void* norms, int64_t n_vec, int32_t io_dtype,
+                            int32_t meta_dtype, uint32_t flags, void* stream) {
+  if (!x || !out || n_vec < 0) return OSCAR_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(OSCAR_ROTATE_NORMALIZE | OSCAR_ROTATE_FAST_RSQRT)) return OSCAR_ERR_INVALID_ARG;
+  if ((flags & OSCAR_ROTATE_FAST_RSQRT) && !(flags & OSCAR_ROTATE_NORMALIZE)) return OSCAR_ERR_INVALID_ARG;
+  if ((flags & OSCAR_ROTATE_NORMALIZE) && !norms) return OSCAR_ERR_INVALID_ARG;
+  if (n_vec > ((int64_t)1 << 34)) return OSCAR_ERR_INVALID_ARG;
+  if (n_vec == 0) return OSCAR_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int rc;
+  switch (io_dtype) {
+    case OSCAR_F32: rc = launch_rotate<float>(x, out, norms, n_vec, meta_dtype, flags, st); break;
+    case OSCAR_BF16: rc = launch_rotate<__hip_bfloat16>(x, out, norms, n_vec, meta_dtype, flags, st); break;
+    case OSCAR_F16: rc = launch_rotate<__half>(x, out, norms, n_vec, meta_dtype, flags, st); break;
+    default: return OSCAR_ERR_INVALID_ARG;
+  }
+  if (rc != OSCAR_OK) return rc;
+  if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+  return OSCAR_OK;
+}
 
 extern "C" int oscar_quantize_append(const void* k, const void* v, int32_t T,
                                      const int32_t* new_lens, oscar_cache* cache,

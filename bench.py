@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
     ap.add_argument("--bf16-splits", type=int, default=0, help="override the comparator's split-K factor")
+    ap.add_argument("--sweep", choices=["context", "batch"], default=None,
+                    help="run the context sweep (batch 1) or the batch sweep (4K context) instead "
+                         "of one workload; prints one JSON object with a list of points")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 256 MiB five times, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE by a known size")
@@ -112,6 +115,30 @@ def main():
     if args.context or args.batch:
         w = w.replace(context=args.context or w.context, batch=args.batch or w.batch,
                       name="%s-b%d-s%d" % (w.name, args.batch or w.batch, args.context or w.context))
+    if args.sweep:
+        # the shape of the paper's efficiency figures: context sweep at batch 1, batch sweep at
+        # 4K context, on the chosen workload's heads; one compact record per point
+        base = w
+        points = ([(1, s) for s in (1024, 4096, 16384, 32768, 65536, 131072)] if args.sweep == "context"
+                  else [(b, 4096) for b in (1, 4, 16, 64, 128)])
+        rows = []
+        for (bb, ss) in points:
+            wp = base.replace(batch=bb, context=ss, name="%s-b%d-s%d" % (base.name, bb, ss))
+            args.no_cpu_baseline = True
+            r = measure(args, wp, np, torch, ob, synth)
+            rows.append({"batch": bb, "context": ss, "splits": r["config"]["splits"],
+                         "us_per_step": r["value"], "partial_us": r["roofline"]["avg_kernel_us"],
+                         "frac": r["roofline"]["frac"],
+                         "bf16_us": r.get("bf16_decode", {}).get("us_per_step"),
+                         "prefill_us": r["quantize_append_prefill"]["us"],
+                         "cache_mb": r["resident_cache_bytes"] / 1e6})
+            torch.cuda.empty_cache()
+        print(json.dumps({"sweep": args.sweep, "workload": base.name, "bits": base.bits, "points": rows}))
+        return
+    print(json.dumps(measure(args, w, np, torch, ob, synth)))
+
+
+def measure(args, w, np, torch, ob, synth):
     io = {"f32": ob.F32, "bf16": ob.BF16, "f16": ob.F16}[w.io_dtype]
     meta = {"f32": ob.F32, "f16": ob.F16}[w.meta_dtype]
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
@@ -125,7 +152,8 @@ def main():
     bytes_tok = synth.cache_bytes_per_token_kvh(w)
     units = w.batch * w.n_kv_heads * (w.context // R) * R      # packed token-heads read per step
     cache_bytes = units * bytes_tok
-    n_copies = args.copies or max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1)
+    # (small caches: at most 32 copies, i.e. those points run warm in the last-level cache)
+    n_copies = args.copies or min(32, max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1))
 
     # ---- prefill: quantize_append of the whole context, timed per copy ----
     caches, t_pre = [], []
@@ -312,7 +340,7 @@ def main():
             res["kernel_speedup_vs_bf16_at_stream_probe_rate"] = ideal_us / k_us
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, kd, vd, q_host, cfg)
-    print(json.dumps(res))
+    return res
 
 
 if __name__ == "__main__":

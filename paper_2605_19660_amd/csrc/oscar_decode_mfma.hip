@@ -33,6 +33,7 @@
 #include <stdlib.h>
 
 #include "oscar_decode_common.h"
+#include "oscar_rowops.h"
 
 namespace {
 
@@ -308,42 +309,54 @@ template <int BITS, int NGV> struct ValRegs {
   }
 };
 
-// One residual token's share for a lane: 8 channels of K_u (fp16), of V (caller's dtype),
-// and the token norm, held raw until the query rotation is done.
-struct ResTok {
-  uint4 k, v0, v1;
-  uint32_t nrm;
-  __device__ __forceinline__ void load(const DecodeParams& P, const __half* rk, size_t rb, int t_lo,
-                                       int t, int rcount, int n) {
-    k = v0 = v1 = make_uint4(0u, 0u, 0u, 0u);
-    nrm = 0u;
-    if (t < rcount) {
-      const size_t tok = rb + t_lo + t;
-      k = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * n);
-      if (P.c.cfg.io_dtype == OSCAR_F32) {
-        const uint4* vp = reinterpret_cast<const uint4*>(static_cast<const float*>(P.c.res_v) + tok * D + 8 * n);
-        v0 = vp[0];
-        v1 = vp[1];
-      } else {
-        v0 = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(P.c.res_v) + tok * D + 8 * n);
-      }
-      if (P.g.meta_bytes == 4) nrm = static_cast<const uint32_t*>(P.c.res_norm)[tok];
-      else nrm = static_cast<const uint16_t*>(P.c.res_norm)[tok];
+// Eight consecutive values of the caller's dtype (a run-time property here), held raw.
+struct Raw8rt {
+  uint4 a, b;
+  __device__ __forceinline__ void zero() { a = b = make_uint4(0u, 0u, 0u, 0u); }
+  __device__ __forceinline__ void load(const void* p, size_t idx, int dt) {
+    if (dt == OSCAR_F32) {
+      const uint4* vp = reinterpret_cast<const uint4*>(static_cast<const float*>(p) + idx);
+      a = vp[0];
+      b = vp[1];
+    } else {
+      a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + idx);
+      b = a;
     }
   }
-  __device__ __forceinline__ void values(float (&x)[8], int dt) const {
+  __device__ __forceinline__ void widen(float (&x)[8], int dt) const {
     if (dt == OSCAR_F32) {
-      x[0] = __uint_as_float(v0.x); x[1] = __uint_as_float(v0.y);
-      x[2] = __uint_as_float(v0.z); x[3] = __uint_as_float(v0.w);
-      x[4] = __uint_as_float(v1.x); x[5] = __uint_as_float(v1.y);
-      x[6] = __uint_as_float(v1.z); x[7] = __uint_as_float(v1.w);
+      x[0] = __uint_as_float(a.x); x[1] = __uint_as_float(a.y);
+      x[2] = __uint_as_float(a.z); x[3] = __uint_as_float(a.w);
+      x[4] = __uint_as_float(b.x); x[5] = __uint_as_float(b.y);
+      x[6] = __uint_as_float(b.z); x[7] = __uint_as_float(b.w);
     } else if (dt == OSCAR_BF16) {
-      x[0] = __uint_as_float(v0.x << 16); x[1] = __uint_as_float(v0.x & 0xffff0000u);
-      x[2] = __uint_as_float(v0.y << 16); x[3] = __uint_as_float(v0.y & 0xffff0000u);
-      x[4] = __uint_as_float(v0.z << 16); x[5] = __uint_as_float(v0.z & 0xffff0000u);
-      x[6] = __uint_as_float(v0.w << 16); x[7] = __uint_as_float(v0.w & 0xffff0000u);
+      x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+      x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+      x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
+      x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
     } else {
-      halves_to_f32(v0, x);
+      halves_to_f32(a, x);
+    }
+  }
+};
+
+// One residual token's share for a lane: 8 channels (channel group cg) of K_u (fp16) and of
+// V (caller's dtype), and the token norm, held raw until the query rotation is done.
+struct ResTok {
+  uint4 k;
+  Raw8rt v;
+  uint32_t nrm;
+  __device__ __forceinline__ void load(const DecodeParams& P, const __half* rk, size_t rb, int t_lo,
+                                       int t, int rcount, int cg) {
+    k = make_uint4(0u, 0u, 0u, 0u);
+    v.zero();
+    nrm = 0u;
+    if (t < rcount) {   // wave-uniform
+      const size_t tok = rb + t_lo + t;
+      k = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * cg);
+      v.load(P.c.res_v, tok * D + 8 * cg, P.c.cfg.io_dtype);
+      if (P.g.meta_bytes == 4) nrm = static_cast<const uint32_t*>(P.c.res_norm)[tok];
+      else nrm = static_cast<const uint16_t*>(P.c.res_norm)[tok];
     }
   }
 };
@@ -382,7 +395,6 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
   constexpr int CPG = 8 / NGV;  // channel tiles per value group
   constexpr int TABW = D + 8;   // operand table row stride in halves
 
-  __shared__ __align__(16) float s_q[OSCAR_MAX_GQA][D];
   // rows padded by 16 bytes: the 16-byte operand reads of lanes n = 0..7 hit 8 different banks
   __shared__ __align__(16) _Float16 s_A[4][16][TABW];   // per wave: (Q_h Delta_k) hi/lo rows
   __shared__ __align__(16) _Float16 s_P[4][16][TABW];   // per wave: (p Delta_v) hi/lo rows
@@ -411,14 +423,16 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
     return idx < P.c.max_pages_per_seq ? table[idx] : 0;
   };
   int tab = load_table(0);
-  // queries of the heads this wave rotates (w and w+4): channels (lane, lane+64)
-  float qx[2][2];
+  // queries: DPP row q4 of every wave takes head q4 (and q4 + 4 in the second slot), 8
+  // channels (channel group cg) per lane; absent heads read as zeros
+  const int cg = channel_group_of_row_lane(n);
+  Raw8rt qraw[HP];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int h = min(wave + 4 * i, gq - 1);
-    const size_t qb = ((size_t)b * Hq + (size_t)kvh * gq + h) * D;
-    qx[i][0] = load_io(P.q, qb + lane, P.c.cfg.io_dtype);
-    qx[i][1] = load_io(P.q, qb + lane + 64, P.c.cfg.io_dtype);
+  for (int s = 0; s < HP; ++s) {
+    const int h = q4 + 4 * s;
+    qraw[s].zero();
+    if (h < gq)
+      qraw[s].load(P.q, ((size_t)b * Hq + (size_t)kvh * gq + h) * D + 8 * cg, P.c.cfg.io_dtype);
   }
 
   const int seq_len = P.c.seq_lens[b];
@@ -442,34 +456,27 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
   }
   const size_t rb = ((size_t)b * Hkv + kvh) * R;
   const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
-  ResTok rt_first;
-  rt_first.load(P, rk, rb, t_lo, 4 * wave + q4, rcount, n);
+  ResTok rt_first[4];   // the wave's four tokens of the first residual pass
+#pragma unroll
+  for (int i = 0; i < 4; ++i) rt_first[i].load(P, rk, rb, t_lo, 4 * wave + i, rcount, cg);
 
-  // zero the operand tables (rows of absent heads stay zero)
-  for (int i = tid; i < 4 * 16 * TABW / 8; i += 256) {
-    reinterpret_cast<uint4*>(&s_A[0][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
-    reinterpret_cast<uint4*>(&s_P[0][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
+  // this wave's operand tables start as zeros (rows of absent heads stay zero)
+  for (int i = lane; i < 16 * TABW / 8; i += 64) {
+    reinterpret_cast<uint4*>(&s_A[wave][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
+    reinterpret_cast<uint4*>(&s_P[wave][0][0])[i] = make_uint4(0u, 0u, 0u, 0u);
   }
-  // Q_h = H(q)/sqrt(128) * scale*log2(e): wave w rotates heads w and w+4 on its own; a lane
-  // holds channels (lane, lane+64): stage 64 in registers, stages 1..32 across lanes.
+  // Q_h = H(q)/sqrt(128) * scale*log2(e), every wave for itself (DPP butterflies inside the
+  // row, no LDS, no workgroup barrier): qh[s][i] = channel 8*cg + i of head q4 + 4*s
+  uint32_t sgn[4];
+  butterfly_signs(cg, sgn);
+  float qh[HP][8];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int h = wave + 4 * i;
-    float x0 = qx[i][0], x1 = qx[i][1];
+  for (int s = 0; s < HP; ++s) {
+    qraw[s].widen(qh[s], P.c.cfg.io_dtype);
+    rotate8(qh[s], sgn);
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      const float y0 = __shfl_xor(x0, m, 64), y1 = __shfl_xor(x1, m, 64);
-      const bool up = (lane & m) != 0;
-      x0 = up ? y0 - x0 : x0 + y0;
-      x1 = up ? y1 - x1 : x1 + y1;
-    }
-    const float c = 0.08838834764831845f * P.qk_scale_log2;
-    if (h < gq) {
-      s_q[h][lane] = (x0 + x1) * c;
-      s_q[h][lane + 64] = (x0 - x1) * c;
-    }
+    for (int i = 0; i < 8; ++i) qh[s][i] *= P.qk_scale_log2;
   }
-  __syncthreads();
 
   // ---- wave state: online softmax over this wave's pages, seeded by its residual tokens ----
   float m_run[HP], l_run[HP], bv[HP][NGV];
@@ -486,71 +493,64 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
   // accumulator scale: O holds out * 2^-(24 - xv_cur - offset); this start value makes it 1
   int xv_cur = 24 - slot_bitpos_min(BITS);
 
-  // ---- residual tokens: plain-ALU attention over fp16 K_u and raw V, wave-local.  A lane
-  // is (token j = lane/16 of the wave's four, channels 8n..8n+7); logits are reduced over
-  // the 16 lanes of a row, the softmax state over the four rows.  The result becomes the
-  // starting state of the wave's accumulators, so it costs no workgroup barrier. ----
+  // ---- residual tokens: plain-ALU attention over fp16 K_u and raw V, wave-local.  Row q4
+  // works for head q4 (+4) on all four tokens of the wave's pass, a lane on its 8 channels:
+  // logits are reduced over the 16 lanes of the row, nothing crosses rows.  The result
+  // becomes the starting state of the wave's accumulators, so it costs no barrier. ----
   if (wave_res) {
-    constexpr int NH = 4 * HP;
-    float mw[NH], lw[NH], ow[NH][8];
+    float mw[HP], lw[HP], ow[HP][8];
 #pragma unroll
-    for (int h = 0; h < NH; ++h) {
-      mw[h] = -INFINITY;
-      lw[h] = 0.0f;
+    for (int s = 0; s < HP; ++s) {
+      mw[s] = -INFINITY;
+      lw[s] = 0.0f;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) ow[h][c] = 0.0f;
+      for (int c = 0; c < 8; ++c) ow[s][c] = 0.0f;
     }
     for (int p0 = 0; p0 + 4 * wave < rcount; p0 += 16) {
-      ResTok rt = rt_first;
-      if (p0 > 0) rt.load(P, rk, rb, t_lo, p0 + 4 * wave + q4, rcount, n);
-      const bool valid = p0 + 4 * wave + q4 < rcount;
-      float kv[8], vv[8];
-      halves_to_f32(rt.k, kv);
-      rt.values(vv, P.c.cfg.io_dtype);
-      const float nrm = valid ? load_meta_bits(rt.nrm, P.g.meta_bytes) : 0.0f;
+      float sc[HP][4], vv[4][8];
 #pragma unroll
-      for (int h = 0; h < NH; ++h) {
-        if (h < gq) {
-          const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][8 * n]);
-          const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][8 * n + 4]);
-          float acc = qa.x * kv[0];
-          acc = fmaf(qa.y, kv[1], acc);
-          acc = fmaf(qa.z, kv[2], acc);
-          acc = fmaf(qa.w, kv[3], acc);
-          acc = fmaf(qb.x, kv[4], acc);
-          acc = fmaf(qb.y, kv[5], acc);
-          acc = fmaf(qb.z, kv[6], acc);
-          acc = fmaf(qb.w, kv[7], acc);
-          const float sc = valid ? nrm * row16_sum(acc) : -INFINITY;
-          float mx = fmaxf(sc, __shfl_xor(sc, 16, 64));
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-          // the wave's first token (row 0 of its first pass) is valid, so mx is finite
-          const float m_new = fmaxf(mw[h], mx);
-          const float alpha = __builtin_amdgcn_exp2f(mw[h] - m_new);
-          const float pw = __builtin_amdgcn_exp2f(sc - m_new);
-          mw[h] = m_new;
-          lw[h] = lw[h] * alpha + pw;
+      for (int i = 0; i < 4; ++i) {
+        ResTok rt = rt_first[i];
+        if (p0 > 0) rt.load(P, rk, rb, t_lo, p0 + 4 * wave + i, rcount, cg);
+        const bool valid = p0 + 4 * wave + i < rcount;   // wave-uniform
+        float kv[8];
+        halves_to_f32(rt.k, kv);
+        rt.v.widen(vv[i], P.c.cfg.io_dtype);
+        const float nrm = load_meta_bits(rt.nrm, P.g.meta_bytes);
 #pragma unroll
-          for (int c = 0; c < 8; ++c) ow[h][c] = fmaf(pw, vv[c], ow[h][c] * alpha);
+        for (int s = 0; s < HP; ++s) {
+          float acc = qh[s][0] * kv[0];
+#pragma unroll
+          for (int c = 1; c < 8; ++c) acc = fmaf(qh[s][c], kv[c], acc);
+          sc[s][i] = valid ? nrm * row16_sum(acc) : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < HP; ++s) {
+        // the wave's first token of a pass is valid, so the maximum is finite
+        const float m_new = fmaxf(fmaxf(mw[s], fmaxf(sc[s][0], sc[s][1])), fmaxf(sc[s][2], sc[s][3]));
+        const float alpha = __builtin_amdgcn_exp2f(mw[s] - m_new);
+        mw[s] = m_new;
+        lw[s] *= alpha;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) ow[s][c] *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pw = __builtin_amdgcn_exp2f(sc[s][i] - m_new);
+          lw[s] += pw;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) ow[s][c] = fmaf(pw, vv[i][c], ow[s][c]);
         }
       }
     }
-    // sum the four rows, hand the result over in accumulator layout through the wave's
-    // own slice of s_o (written again only by this wave, at the very end)
+    // hand the result over in accumulator layout through the wave's own slice of s_o
+    // (written again only by this wave: for the query hand-off below and at the very end)
 #pragma unroll
-    for (int h = 0; h < NH; ++h) {
+    for (int s = 0; s < HP; ++s) {
+      const int h = q4 + 4 * s;
       if (h < gq) {
-        lw[h] += __shfl_xor(lw[h], 16, 64);
-        lw[h] += __shfl_xor(lw[h], 32, 64);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          ow[h][c] += __shfl_xor(ow[h][c], 16, 64);
-          ow[h][c] += __shfl_xor(ow[h][c], 32, 64);
-        }
-        if (q4 == 0) {
-          *reinterpret_cast<float4*>(&s_o[wave][h][8 * n]) = make_float4(ow[h][0], ow[h][1], ow[h][2], ow[h][3]);
-          *reinterpret_cast<float4*>(&s_o[wave][h][8 * n + 4]) = make_float4(ow[h][4], ow[h][5], ow[h][6], ow[h][7]);
-        }
+        *reinterpret_cast<float4*>(&s_o[wave][h][8 * cg]) = make_float4(ow[s][0], ow[s][1], ow[s][2], ow[s][3]);
+        *reinterpret_cast<float4*>(&s_o[wave][h][8 * cg + 4]) = make_float4(ow[s][4], ow[s][5], ow[s][6], ow[s][7]);
       }
     }
     wave_lds_fence();
@@ -558,21 +558,24 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
     for (int s = 0; s < HP; ++s) {
       const int h = q4 + 4 * s;
       if (h < gq) {
-        // (the compiler selects mw[h], lw[h] by q4; NH is at most 8)
-        float mh = mw[0], lh = lw[0];
-#pragma unroll
-        for (int hh = 1; hh < NH; ++hh) {
-          mh = (hh == h) ? mw[hh] : mh;
-          lh = (hh == h) ? lw[hh] : lh;
-        }
-        m_run[s] = mh;
-        l_run[s] = (n == 0) ? lh : 0.0f;   // l_run is summed over the 16 lanes at the end
+        m_run[s] = mw[s];
+        l_run[s] = (n == 0) ? lw[s] : 0.0f;   // l_run is summed over the 16 lanes at the end
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) O[ct][2 * s] = s_o[wave][h][16 * ct + n];
       }
     }
     wave_lds_fence();
   }
+  // rotated queries -> operand order, through the same wave-local slice
+#pragma unroll
+  for (int s = 0; s < HP; ++s) {
+    const int h = q4 + 4 * s;
+    if (h < gq) {
+      *reinterpret_cast<float4*>(&s_o[wave][h][8 * cg]) = make_float4(qh[s][0], qh[s][1], qh[s][2], qh[s][3]);
+      *reinterpret_cast<float4*>(&s_o[wave][h][8 * cg + 4]) = make_float4(qh[s][4], qh[s][5], qh[s][6], qh[s][7]);
+    }
+  }
+  wave_lds_fence();
 
   // ---- per-lane constants ----
   // writer role for the key operand: positions 8n..8n+7 of heads q4 (+4)
@@ -584,7 +587,7 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int chan = 32 * (n >> 2) + slot_index(BITS, n & 3, i);
-      qr[s][i] = (h < gq) ? s_q[h][chan] : 0.0f;
+      qr[s][i] = (h < gq) ? s_o[wave][h][chan] : 0.0f;
       mx = fmaxf(mx, fabsf(qr[s][i]));
     }
     mx = row16_max(mx);

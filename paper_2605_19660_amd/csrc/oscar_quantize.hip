@@ -27,6 +27,7 @@
 // fp32 with their place values (exact: small integers) and converted once.  Both code
 // images are built in LDS in their final page layout and leave with 16-byte stores.
 #include "oscar_common.h"
+#include "oscar_rowops.h"
 
 namespace {
 
@@ -114,16 +115,6 @@ __device__ __forceinline__ uint32_t half_bits(float x) {
   return (uint32_t)__half_as_ushort(__float2half_rn(x));
 }
 
-// Value of the lane whose channel group differs in bit STAGE (0..3), inside the 16-lane
-// row of a token.  Row lane r holds channel group cg = (r0^r2) | (r1^r2)<<1 | r2<<2 | r3<<3.
-template <int STAGE> __device__ __forceinline__ float partner(float v) {
-  constexpr int ctrl = STAGE == 0 ? 0xB1     // quad_perm [1,0,3,2]: r ^ 1
-                     : STAGE == 1 ? 0x4E     // quad_perm [2,3,0,1]: r ^ 2
-                     : STAGE == 2 ? 0x141    // row_half_mirror:     r ^ 7
-                                  : 0x128;   // row_ror:8:           r ^ 8
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
-}
 // value of lane j (a constant after unrolling) of the caller's quad
 template <int CTRL> __device__ __forceinline__ float dpp_read(float v) {
   return __builtin_bit_cast(
@@ -137,42 +128,6 @@ __device__ __forceinline__ float quad_bcast(float v, int j) {
     default: return dpp_read<0xFF>(v);
   }
 }
-__device__ __forceinline__ int channel_group_of_row_lane(int r) {
-  const int b2 = (r >> 2) & 1;
-  return ((r ^ b2) & 1) | ((((r >> 1) ^ b2) & 1) << 1) | (b2 << 2) | (r & 8);
-}
-
-// Key transform of 8 channels of one token held by 16 cooperating lanes:
-// K_h = H(k)/sqrt(128), n = ||K_h||_2 rounded to the metadata type, K_u = K_h / n
-// rounded to fp16 (returned packed).  Butterfly stage h pairs (i, i|h): lower <- a+b,
-// upper <- a-b; across lanes that is partner + own, with the own value negated in the
-// upper lane (sgn[stage] = sign bit there, 0 in the lower lane).
-// H(x)/sqrt(128) of the 8 channels a lane holds (128 channels over the 16 lanes of a row).
-__device__ __forceinline__ void rotate8(float (&x)[8], const uint32_t (&sgn)[4]) {
-#pragma unroll
-  for (int h = 1; h < 8; h <<= 1) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if ((i & h) == 0) {
-        float a = x[i], b = x[i | h];
-        x[i] = a + b;
-        x[i | h] = a - b;
-      }
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<0>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[0]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<1>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[1]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<2>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[2]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<3>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[3]);
-  const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = x[i] * c;
-}
-
 // sum of squares of the 128 rotated channels: balanced tree, adjacent pairs first
 __device__ __forceinline__ float row_sumsq(const float (&x)[8]) {
   float t[8];

@@ -156,10 +156,10 @@ float io_at(const std::vector<uint8_t>& buf, size_t idx, int dt) {
 }
 }  // namespace
 
-extern "C" int oscar_debug_dump(const oscar_cache* c, int32_t b, int32_t h, int32_t cap_tokens,
-                                uint8_t* k_codes, float* k_delta, float* k_zero, float* k_norm,
-                                uint8_t* v_codes, float* v_delta, float* v_zero, float* res_k,
-                                float* res_v, float* res_norm, int32_t* lens, void* stream) {
+static int debug_dump_impl(const oscar_cache* c, int32_t b, int32_t h, int32_t cap_tokens,
+                           uint8_t* k_codes, float* k_delta, float* k_zero, float* k_norm,
+                           uint8_t* v_codes, float* v_delta, float* v_zero, float* res_k,
+                           float* res_v, float* res_norm, int32_t* lens, void* stream) {
   if (!c) return OSCAR_ERR_INVALID_ARG;
   int rc = oscar_validate_config(&c->cfg);
   if (rc != OSCAR_OK) return rc;
@@ -243,4 +243,17 @@ extern "C" int oscar_debug_dump(const oscar_cache* c, int32_t b, int32_t h, int3
     for (int i = 0; i < R; ++i) res_norm[i] = meta_at(buf, (size_t)i, c->cfg.meta_dtype);
   }
   return OSCAR_OK;
+}
+
+// No C++ exception crosses the C boundary: a failed host allocation is reported as a status.
+extern "C" int oscar_debug_dump(const oscar_cache* c, int32_t b, int32_t h, int32_t cap_tokens,
+                                uint8_t* k_codes, float* k_delta, float* k_zero, float* k_norm,
+                                uint8_t* v_codes, float* v_delta, float* v_zero, float* res_k,
+                                float* res_v, float* res_norm, int32_t* lens, void* stream) {
+  try {
+    return debug_dump_impl(c, b, h, cap_tokens, k_codes, k_delta, k_zero, k_norm, v_codes, v_delta,
+                           v_zero, res_k, res_v, res_norm, lens, stream);
+  } catch (...) {
+    return OSCAR_ERR_HIP;
+  }
 }

@@ -193,6 +193,48 @@ def test_decode_gqa_variants_split_and_page_permutation_invariance(hq, hkv, bits
     assert torch.equal(ob16.float().cpu(), torch.from_numpy(outs[2]).to(torch.bfloat16).float())
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_decode_long_stream_one_split_crosses_block_table_chunks(bits):
+    """One split over 300 pages: every wave walks 75 pages, more than the 64 block-table entries
+    it keeps in a register, with a shuffled block table; a full (deferred) residual on top."""
+    ob = _ob()
+    n_pages = 300
+    w = synth.LLAMA8B_32K.replace(batch=1, n_q_heads=4, n_kv_heads=1, context=128 * n_pages + 128,
+                                  bits=bits)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    rng = np.random.default_rng(11)
+    g, o = make_pair(w, n_pages + 2, page_perm=rng.permutation(n_pages + 2))
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    ob.quantize_append(g, kd, vd)          # deferred rule: the last 128 tokens stay 16-bit
+    o.append(k, v)
+    assert int(o.n_res[0]) == 128 and int(o.n_packed[0]) == 128 * n_pages
+    want = o.decode_attn(q)
+    for splits in (1, 2):
+        out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=w.context, num_splits=splits)
+        assert_decode_close(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -12, 2.0 ** 6])
+def test_decode_extreme_value_magnitudes(scale):
+    """Values (and so their step sizes) far from 1: the per-page power-of-two operand scaling of
+    the matrix-core path has to follow; tolerance relative to the output scale."""
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 6 + 40, io_dtype="f16")
+    k, v = synth.make_kv_batch(w)
+    v = (v * scale).astype(np.float32)
+    v = np.asarray(to_dev(v, "f16").float().cpu().numpy())     # what fp16 holds
+    assert np.isfinite(v).all()
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8)
+    ob.quantize_append(g, to_dev(k, "f16"), to_dev(v, "f16"), eager=True)
+    o.append(k, v, eager=True)
+    assert_cache_equal(g, o, w)
+    got = ob.decode_attn(g, to_dev(q, "f16"), max_seq_len_hint=w.context).cpu().numpy()
+    want = o.decode_attn(q)
+    assert_decode_close(got / scale, want / scale)
+
+
 def test_decode_edge_cases_empty_residual_only_and_exact_pages():
     torch = _torch()
     ob = _ob()

@@ -1,12 +1,14 @@
 // 16-bit comparator: split-K decode attention softmax(q K^T) V on an uncompressed,
 // un-rotated cache, token-major [batch][tokens][kv heads][128] or head-major
 // [batch][kv heads][tokens][128] (the BF16 FlashDecoding-style baseline of the paper's
-// efficiency section).  Same split / partial / reduce
-// skeleton as the compressed path, 512 bytes per token and kv head.
+// efficiency section).  Same split / partial / reduce skeleton as the compressed path,
+// 512 bytes per token and kv head.
 //
-// Tile = 64 tokens.  Keys go global -> LDS with 16-byte coalesced loads (padded rows),
-// 4 lanes share a token for the dot products; values are read straight from global,
-// 32 lanes x 8 bytes per token row, 8 token phases reduced through LDS at the end.
+// A 16-lane DPP row owns a token at a time (lane = 8 channels, the query slice of every head
+// of the group in registers), walks tokens row, row+16, ... of the split with its own online
+// softmax state, four tokens per step and the next four already in flight; logits reduce
+// inside the row, nothing is shared until the 16 row states merge through LDS at the end.
+// With a head-major cache a wave's four rows read 1 KB of consecutive memory per load.
 #include <string.h>
 
 #include "oscar_common.h"
@@ -14,9 +16,8 @@
 namespace {
 
 constexpr int D = OSCAR_D;
-constexpr int TILE = 64;
-constexpr int KROW = D * 2 + 16;  // padded LDS row, bytes
 constexpr int WS_STRIDE = D + 2;
+constexpr int TOK_STEP = 4;   // tokens per row and step
 
 struct PlainParams {
   const void* q;
@@ -36,174 +37,162 @@ template <> __device__ __forceinline__ float cvt16<__hip_bfloat16>(uint32_t b) {
 template <> __device__ __forceinline__ float cvt16<__half>(uint32_t b) {
   return __half2float(__ushort_as_half((unsigned short)b));
 }
-
-__device__ __forceinline__ float wave_max(float v) {
+template <typename T> __device__ __forceinline__ void widen8(const uint4& r, float (&x)[8]) {
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-  return v;
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = cvt16<T>(w[i] & 0xffffu);
+    x[2 * i + 1] = cvt16<T>(w[i] >> 16);
+  }
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+
+template <int CTRL> __device__ __forceinline__ float dpp_get(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// sum over the 16 lanes of a DPP row; every lane ends with the total
+__device__ __forceinline__ float row_sum16(float v) {
+  v += dpp_get<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_get<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_get<0x141>(v);  // row_half_mirror
+  v += dpp_get<0x140>(v);  // row_mirror
   return v;
 }
 
 template <typename T, int GQ>
 __global__ __launch_bounds__(256) void oscar_plain_decode_partial_kernel(PlainParams P) {
-  __shared__ __align__(16) uint8_t s_k[TILE][KROW];
-  __shared__ __align__(16) float s_q[GQ][D];
-  __shared__ __align__(16) float s_S[GQ][TILE];
-  __shared__ float s_m[GQ], s_l[GQ], s_alpha[GQ];
-  __shared__ __align__(16) float s_o[8][GQ][D];
+  __shared__ float s_m[16][GQ], s_l[16][GQ];
+  __shared__ __align__(16) float s_o[16][GQ][D];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, row = tid >> 4, n = tid & 15;
   const int len = min(P.seq_lens ? P.seq_lens[b] : P.S, P.S);
-  const int n_tiles = (len + TILE - 1) / TILE;
-  const int tps = (n_tiles + P.num_splits - 1) / P.num_splits;
-  const int t0 = split * tps, t1 = min(n_tiles, t0 + tps);
+  // token range of this split, in multiples of 64
+  const int per_split = ((len + P.num_splits - 1) / P.num_splits + 63) & ~63;
+  const int tok0 = split * per_split, tok1 = min(len, tok0 + per_split);
 
-  for (int i = tid; i < GQ * D; i += 256) {
-    const uint16_t raw = reinterpret_cast<const uint16_t*>(P.q)[((size_t)b * P.Hq + (size_t)kvh * GQ) * D + i];
-    s_q[i / D][i % D] = cvt16<T>(raw) * P.qk_scale_log2;
+  // query slices, scaled: channels 8n..8n+7 of every head of the group
+  float qf[GQ][8];
+#pragma unroll
+  for (int h = 0; h < GQ; ++h) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(
+        reinterpret_cast<const uint16_t*>(P.q) + ((size_t)b * P.Hq + (size_t)kvh * GQ + h) * D + 8 * n);
+    widen8<T>(raw, qf[h]);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qf[h][c] *= P.qk_scale_log2;
   }
-  if (tid < GQ) {
-    s_m[tid] = -INFINITY;
-    s_l[tid] = 0.0f;
+  float m[GQ], l[GQ], o[GQ][8];
+#pragma unroll
+  for (int h = 0; h < GQ; ++h) {
+    m[h] = -INFINITY;
+    l[h] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[h][c] = 0.0f;
   }
-  float o[GQ][4];
-#pragma unroll
-  for (int h = 0; h < GQ; ++h)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[h][e] = 0.0f;
-  __syncthreads();
 
-  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(P.k);
-  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(P.v);
-  // bytes between consecutive tokens of one kv head, and offset of this stream
-  const size_t row_stride = P.head_major ? (size_t)D * 2 : (size_t)P.Hkv * D * 2;
-  const size_t seq_off = P.head_major ? ((size_t)b * P.Hkv + kvh) * P.S * D * 2
-                                      : ((size_t)b * P.S * P.Hkv + kvh) * D * 2;
-
-  const int tok = tid >> 2, quarter = tid & 3;  // logits: 4 lanes per token
-  const int c4 = tid & 31, tg = tid >> 5;       // values: 4 channels per lane, 8 token phases
-
-  for (int tile = t0; tile < t1; ++tile) {
-    const int base = tile * TILE;
-    // keys -> LDS (1024 x 16 bytes)
+  if (tok0 < tok1) {
+    const uint8_t* kbase = reinterpret_cast<const uint8_t*>(P.k);
+    const uint8_t* vbase = reinterpret_cast<const uint8_t*>(P.v);
+    // bytes between consecutive tokens of one kv head, and offset of this stream
+    const size_t row_stride = P.head_major ? (size_t)D * 2 : (size_t)P.Hkv * D * 2;
+    const size_t seq_off = (P.head_major ? ((size_t)b * P.Hkv + kvh) * P.S * D * 2
+                                         : ((size_t)b * P.S * P.Hkv + kvh) * D * 2) + n * 16;
+    // this row's tokens: tok0 + row + 16 * i; positions past the end are read from the last
+    // valid token and masked
+    auto load_step = [&](int t_first, uint4 (&kr)[TOK_STEP], uint4 (&vr)[TOK_STEP]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = tid + i * 256;
-      const int t = idx >> 4, part = idx & 15;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (base + t < len)
-        val = *reinterpret_cast<const uint4*>(kbase + seq_off + (size_t)(base + t) * row_stride + part * 16);
-      *reinterpret_cast<uint4*>(&s_k[t][part * 16]) = val;
-    }
-    // values: issue early, 8 token rows x 8 bytes
-    uint2 vraw[8];
+      for (int j = 0; j < TOK_STEP; ++j) {
+        const int t = min(t_first + 16 * j, tok1 - 1);
+        kr[j] = *reinterpret_cast<const uint4*>(kbase + seq_off + (size_t)t * row_stride);
+        vr[j] = *reinterpret_cast<const uint4*>(vbase + seq_off + (size_t)t * row_stride);
+      }
+    };
+    uint4 kcur[TOK_STEP], vcur[TOK_STEP];
+    load_step(tok0 + row, kcur, vcur);
+    // uniform trip count for the workgroup (rows past their tokens run masked steps)
+    for (int t_first = tok0 + row; t_first - row < tok1; t_first += 16 * TOK_STEP) {
+      uint4 knext[TOK_STEP], vnext[TOK_STEP];
+      load_step(t_first + 16 * TOK_STEP, knext, vnext);   // clamped: harmless past the end
+      float sc[GQ][TOK_STEP];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int t = tg + 8 * i;
-      vraw[i] = make_uint2(0, 0);
-      if (base + t < len)
-        vraw[i] = *reinterpret_cast<const uint2*>(vbase + seq_off + (size_t)(base + t) * row_stride + c4 * 8);
-    }
-    __syncthreads();
-    {
-      float acc[GQ];
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) acc[h] = 0.0f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(&s_k[tok][quarter * 64 + i * 16]);
-        const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
+      for (int j = 0; j < TOK_STEP; ++j) {
         float kv[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          kv[2 * e] = cvt16<T>(wds[e] & 0xffffu);
-          kv[2 * e + 1] = cvt16<T>(wds[e] >> 16);
-        }
-        const int j = quarter * 32 + i * 8;
+        widen8<T>(kcur[j], kv);
+        const bool valid = t_first + 16 * j < tok1;
 #pragma unroll
         for (int h = 0; h < GQ; ++h) {
-          const float4 qa = *reinterpret_cast<const float4*>(&s_q[h][j]);
-          const float4 qb = *reinterpret_cast<const float4*>(&s_q[h][j + 4]);
-          acc[h] = fmaf(qa.x, kv[0], acc[h]);
-          acc[h] = fmaf(qa.y, kv[1], acc[h]);
-          acc[h] = fmaf(qa.z, kv[2], acc[h]);
-          acc[h] = fmaf(qa.w, kv[3], acc[h]);
-          acc[h] = fmaf(qb.x, kv[4], acc[h]);
-          acc[h] = fmaf(qb.y, kv[5], acc[h]);
-          acc[h] = fmaf(qb.z, kv[6], acc[h]);
-          acc[h] = fmaf(qb.w, kv[7], acc[h]);
+          float acc = qf[h][0] * kv[0];
+#pragma unroll
+          for (int c = 1; c < 8; ++c) acc = fmaf(qf[h][c], kv[c], acc);
+          sc[h][j] = valid ? row_sum16(acc) : -INFINITY;
+        }
+      }
+      float pw[GQ][TOK_STEP];
+#pragma unroll
+      for (int h = 0; h < GQ; ++h) {
+        float m_new = m[h];
+#pragma unroll
+        for (int j = 0; j < TOK_STEP; ++j) m_new = fmaxf(m_new, sc[h][j]);
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m[h] - m_safe);
+        m[h] = m_new;
+        l[h] *= alpha;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[h][c] *= alpha;
+#pragma unroll
+        for (int j = 0; j < TOK_STEP; ++j) {
+          pw[h][j] = __builtin_amdgcn_exp2f(sc[h][j] - m_safe);
+          l[h] += pw[h][j];
         }
       }
 #pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        float tot = acc[h] + __shfl_xor(acc[h], 1, 64);
-        tot += __shfl_xor(tot, 2, 64);
-        if (quarter == 0) s_S[h][tok] = (base + tok < len) ? tot : -INFINITY;
+      for (int j = 0; j < TOK_STEP; ++j) {
+        float vv[8];
+        widen8<T>(vcur[j], vv);
+#pragma unroll
+        for (int h = 0; h < GQ; ++h)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) o[h][c] = fmaf(pw[h][j], vv[c], o[h][c]);
+      }
+#pragma unroll
+      for (int j = 0; j < TOK_STEP; ++j) {
+        kcur[j] = knext[j];
+        vcur[j] = vnext[j];
       }
     }
-    __syncthreads();
-    for (int h = wave; h < GQ; h += 4) {
-      const float s0 = s_S[h][lane];
-      const float m_old = s_m[h];
-      const float m_new = fmaxf(m_old, wave_max(s0));
-      const float alpha = exp2f(m_old - m_new);
-      const float p0 = exp2f(s0 - m_new);
-      const float sum = wave_sum(p0);
-      s_S[h][lane] = p0;
-      if (lane == 0) {
-        s_m[h] = m_new;
-        s_l[h] = s_l[h] * alpha + sum;
-        s_alpha[h] = alpha;
-      }
-    }
-    __syncthreads();
-    {
-#pragma unroll
-      for (int h = 0; h < GQ; ++h) {
-        const float al = s_alpha[h];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[h][e] *= al;
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int t = tg + 8 * i;
-        const float v0 = cvt16<T>(vraw[i].x & 0xffffu), v1 = cvt16<T>(vraw[i].x >> 16);
-        const float v2 = cvt16<T>(vraw[i].y & 0xffffu), v3 = cvt16<T>(vraw[i].y >> 16);
-#pragma unroll
-        for (int h = 0; h < GQ; ++h) {
-          const float p = s_S[h][t];
-          o[h][0] = fmaf(p, v0, o[h][0]);
-          o[h][1] = fmaf(p, v1, o[h][1]);
-          o[h][2] = fmaf(p, v2, o[h][2]);
-          o[h][3] = fmaf(p, v3, o[h][3]);
-        }
-      }
-    }
-    __syncthreads();
   }
 
-  // reduce the 8 token phases and write the partial record
+  // merge the 16 row states and write the partial record
 #pragma unroll
-  for (int h = 0; h < GQ; ++h)
-    *reinterpret_cast<float4*>(&s_o[tg][h][c4 * 4]) = make_float4(o[h][0], o[h][1], o[h][2], o[h][3]);
+  for (int h = 0; h < GQ; ++h) {
+    *reinterpret_cast<float4*>(&s_o[row][h][8 * n]) = make_float4(o[h][0], o[h][1], o[h][2], o[h][3]);
+    *reinterpret_cast<float4*>(&s_o[row][h][8 * n + 4]) = make_float4(o[h][4], o[h][5], o[h][6], o[h][7]);
+    if (n == 0) {
+      s_m[row][h] = m[h];
+      s_l[row][h] = l[h];
+    }
+  }
   __syncthreads();
   for (int i = tid; i < GQ * D; i += 256) {
     const int h = i / D, c = i % D;
-    float tot = 0.0f;
+    float M = -INFINITY;
 #pragma unroll
-    for (int g = 0; g < 8; ++g) tot += s_o[g][h][c];
+    for (int r = 0; r < 16; ++r) M = fmaxf(M, s_m[r][h]);
+    float tot = 0.0f, L = 0.0f;
+    if (M != -INFINITY) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float w = (s_m[r][h] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(s_m[r][h] - M);
+        tot = fmaf(s_o[r][h][c], w, tot);
+        L = fmaf(s_l[r][h], w, L);
+      }
+    }
     const size_t rec = ((size_t)b * P.Hq + (size_t)kvh * GQ + h) * P.num_splits + split;
     P.ws[rec * WS_STRIDE + c] = tot;
-  }
-  if (tid < GQ) {
-    const size_t rec = ((size_t)b * P.Hq + (size_t)kvh * GQ + tid) * P.num_splits + split;
-    P.ws[rec * WS_STRIDE + D] = s_m[tid];
-    P.ws[rec * WS_STRIDE + D + 1] = s_l[tid];
+    if (c == 0) {
+      P.ws[rec * WS_STRIDE + D] = M;
+      P.ws[rec * WS_STRIDE + D + 1] = L;
+    }
   }
 }
 

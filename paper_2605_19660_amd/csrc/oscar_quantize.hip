@@ -274,7 +274,10 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   __shared__ __align__(16) MinMax s_red[NGK][4][16];   // [group][wave][channel group]
   __shared__ __align__(16) float4 s_par[NGK][D];       // per channel: 1/Delta, -z, qmax-z, z*place
   __shared__ __align__(16) uint8_t s_kimg[IMG];        // key-code page image
-  __shared__ __align__(16) uint8_t s_vimg[IMG];        // value-code page image
+  // value-code page image, staged with 64 bytes of padding after every eighth of the image:
+  // the lanes of a wave write pieces that are 1/8, 1/4 and 1/2 image apart, which would
+  // otherwise all fall into the same 8 LDS banks
+  __shared__ __align__(16) uint8_t s_vimg[IMG + 8 * 64];
   __shared__ __align__(16) META s_vmeta[2][4][R];
   __shared__ __align__(16) META s_norm[R];
 
@@ -563,7 +566,8 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     for (int e = 0; e < 8; ++e) {
       const int c = 8 * cg + e;
       const uint32_t ev = (uint32_t)(wv0[e] + zv0), od = (uint32_t)(wv1[e] + zv1);
-      const int base = chunk_offset(BITS, c / 16, c % 16, q4);
+      const int lin = chunk_offset(BITS, c / 16, c % 16, q4);
+      const int base = lin + (lin / (IMG / 8)) * 64;
       if (BITS == 2) {
         s_vimg[base + (kk >> 1) * 4 + (kk & 1)] = (uint8_t)ev;
         s_vimg[base + (kk >> 1) * 4 + 2 + (kk & 1)] = (uint8_t)od;
@@ -584,7 +588,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
 #pragma unroll
     for (int i = tid; i < NV; i += 256) {
       kdst[i] = ksrc[i];
-      vdst[i] = vsrc[i];
+      vdst[i] = vsrc[i + (i / (NV / 8)) * 4];   // un-pad: 4 x 16 bytes per eighth
     }
   }
   {

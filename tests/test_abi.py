@@ -70,3 +70,21 @@ def test_null_arguments_are_rejected_before_any_launch():
     cc = ob.Config(32, 8).c()
     assert L.oscar_cache_sizes(C.byref(cc), 1, 1, 1, None) == ob.ERR_INVALID_ARG
     assert ob.decode_workspace_bytes(ob.Config(32, 8), 8, 16) == 8 * 32 * 16 * 130 * 4
+
+
+def test_split_heuristic_and_host_side_argument_checks_of_the_aids():
+    """Host logic that needs no GPU: the split count aims at one round of resident workgroups
+    (two per CU, one for more than 4 query heads per kv head; 256 CUs assumed without a device)
+    and never gives a wave fewer than two pages; the aids reject bad arguments before any launch."""
+    L = ob.lib()
+    assert ob.decode_auto_splits(ob.Config(32, 8), 8, 32768) == 8            # 512 / 64 units
+    assert ob.decode_auto_splits(ob.Config(28, 4), 4, 65536) == 16           # 256 / 16 units (g = 7)
+    assert ob.decode_auto_splits(ob.Config(32, 8), 1, 4096) == 4             # 32 pages / 8
+    assert ob.decode_auto_splits(ob.Config(32, 8), 64, 8192) == 1
+    assert ob.decode_auto_splits(ob.Config(32, 8), 1, 0) == 1
+    assert L.oscar_rotate(None, None, None, 4, ob.BF16, ob.F16, 0, None) == ob.ERR_INVALID_ARG
+    assert L.oscar_probe_stream_read(None, 1 << 20, 4, None, None, None) == ob.ERR_INVALID_ARG
+    assert L.oscar_timer_elapsed_us(None, None) == ob.ERR_INVALID_ARG
+    assert L.oscar_timer_destroy(None) == ob.OK
+    assert L.oscar_bf16_decode_attn(None, None, None, None, None, ob.BF16, ob.F32, 1, 128, 0, 8, 2, 128,
+                                    0.0, 0, 1, None, 0, None) == ob.ERR_INVALID_ARG

@@ -80,23 +80,6 @@ __device__ __forceinline__ void halves_to_f32(const uint4& r, float (&x)[8]) {
   }
 }
 
-__device__ __forceinline__ uint32_t pack_rtz(float a, float b) {
-  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
-}
-
-// fp32 x[8] -> fp16 hi[8] (4 dwords) + fp16 lo[8] with hi + lo = x to ~2^-22
-__device__ __forceinline__ void split_hi_lo(const float (&x)[8], uint4& hi, uint4& lo) {
-  uint32_t h[4], l[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    h[i] = pack_rtz(x[2 * i], x[2 * i + 1]);
-    const half2v hv = __builtin_bit_cast(half2v, h[i]);
-    l[i] = pack_rtz(x[2 * i] - (float)hv[0], x[2 * i + 1] - (float)hv[1]);
-  }
-  hi = make_uint4(h[0], h[1], h[2], h[3]);
-  lo = make_uint4(l[0], l[1], l[2], l[3]);
-}
-
 // fp16 hi[8] + lo[8] limbs of the exact products x[i] * y[i] (y = 8 packed fp16 values):
 // hi = f16(x*y), lo = f16(fma(x, y, -hi)), each a single mixed-precision FMA that reads its
 // fp16 sources in place and writes one half of the destination register, so neither the

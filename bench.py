@@ -193,15 +193,33 @@ def measure(args, w, np, torch, ob, synth):
         ob.decode_attn_partial(c, q, ws, splits, stream=stream, timer=ev)
         ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
 
+    # the first event-carrying launch of a process pays a one-time host cost (tens of ms when
+    # the previous process's memory is still being reclaimed): take it in the warm-up
+    warm_ev = ob.Timer()
     for i in range(args.warmup):
-        step(i)
+        step(i, warm_ev if i == 0 else None)
+    if args.warmup == 0:
+        ob.decode_attn_partial(caches[0], q, ws, splits, stream=stream, timer=warm_ev)
     torch.cuda.synchronize()
+    warm_ev.close()
     evs = [ob.Timer() if i % EV_EVERY == 0 or args.steps < 64 else None for i in range(args.steps)]
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    g0.record(stream)
+    hts = []
     for i in range(args.steps):
         step(args.warmup + i, evs[i])
+        hts.append(time.perf_counter())
+    g1.record(stream)
+    if os.environ.get("OSCAR_BENCH_DEBUG"):
+        d = np.diff(np.array([t0] + hts)) * 1e6
+        print("enqueue us: first", d[:8].round(1), "max", d.max().round(1), "at", int(d.argmax()),
+              "big", [(int(i), float(x.round(0))) for i, x in enumerate(d) if x > 500], file=sys.stderr)
+    t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    gpu_span_us = g0.elapsed_time(g1) * 1e3 / args.steps     # device-side span of the same steps
+    enqueue_us = t_enq / args.steps * 1e6                    # host time to enqueue one step
     us_step = wall / args.steps * 1e6
     k_us = float(np.mean([e.elapsed_us() for e in evs if e is not None]))
     for e in evs:
@@ -318,6 +336,8 @@ def measure(args, w, np, torch, ob, synth):
                      "algorithmic_bytes_per_launch": cache_bytes,
                      "avg_kernel_us": k_us},
         "decode_tokens_per_s": w.batch / (us_step * 1e-6),
+        "device_span_us_per_step": gpu_span_us,
+        "host_enqueue_us_per_step": enqueue_us,
         "cache_bytes_per_token_kv_head": bytes_tok,
         "cache_bytes_per_token_all_heads": bytes_tok * w.n_kv_heads,
         "resident_cache_bytes": cache_bytes,

@@ -32,6 +32,11 @@
  *   [Flow]     same appendix, "Prefill and Decode Workflows" / "Residual
  *              Flush": residual keys are already normalized, flush only
  *              quantizes.
+ *   [Fused-HN] same appendix, "Fused Hadamard-Norm Kernel": all kv heads of a
+ *              token are transformed, their squared sums accumulated across
+ *              heads, one token-wise norm normalizes every head (the
+ *              OREF_NORM_ALL_KV_HEADS variant; [Key-xf]'s per-vector norm is
+ *              the default).
  *
  * Readings taken where the paper is silent (each is listed in the design
  * notes of the repository):
@@ -44,6 +49,9 @@
  *   - max == min: Delta := |min| (1 if that is 0), so a constant group
  *     round-trips exactly.
  *   - zero-norm token: K_u = 0.
+ *   - norm over all kv heads: the per-head squared sums (each in its tree
+ *     order) are added in head order, then one sqrt; the same stored norm is
+ *     kept with every head of the token.
  *
  * Parity status: every function below is pinned by tests under tests/ against
  * closed forms, invariants, the worked example of App. "Detailed Analysis of
@@ -62,6 +70,7 @@
 enum { OREF_F32 = 0, OREF_BF16 = 1, OREF_F16 = 2 };
 enum { OREF_ZP_INT = 0, OREF_ZP_MIN = 1 };
 enum { OREF_SCALE_NONE = 0, OREF_SCALE_L2 = 1 };
+enum { OREF_NORM_PER_HEAD = 0, OREF_NORM_ALL_KV_HEADS = 1 };
 
 typedef struct {
   /* parameters of Alg.1 (G, R, d_h) and of Eq.3-4 (b) */
@@ -74,6 +83,9 @@ typedef struct {
   int32_t zp_mode;    /* OREF_ZP_INT = Eq.3-4 ; OREF_ZP_MIN = float zero-point (cost section of App. complexity) */
   int32_t rotate;     /* 1 = Canalized Rotation on (ablation switch) */
   int32_t scale_mode; /* OREF_SCALE_L2 = Omni-Token Scaling on (ablation switch) */
+  int32_t norm_scope; /* OREF_NORM_PER_HEAD: n = ||K_h|| of one head's vector [Key-xf];
+                         OREF_NORM_ALL_KV_HEADS: one n per token from the squared sums of all
+                         kv heads (the fused preprocessing kernel's description, [Fused-HN]) */
   /* shape */
   int32_t batch, n_kv_heads, cap_tokens; /* cap_tokens multiple of R */
   /* state, per sequence */
@@ -169,6 +181,32 @@ void oref_key_transform(const float *k, int d, int rotate, int scale_mode,
   }
   for (int j = 0; j < d; ++j) u[j] = oref_round_f16(x[j]); /* FP16 residual format [Fmt] */
   *n_st = nf;
+}
+
+/* The token-wise norm of [Fused-HN]: k_heads = the n_heads head vectors of one token
+ * (head h at k_heads + h*head_stride); each head is transformed, its squared sum taken in
+ * the tree order, the sums added in head order; returns the norm rounded to the metadata type. */
+float oref_token_norm_all_heads(const float *k_heads, int n_heads, size_t head_stride, int d,
+                                int rotate, int meta_dtype) {
+  float x[1024];
+  float s = 0.0f;
+  for (int h = 0; h < n_heads; ++h) {
+    for (int j = 0; j < d; ++j) x[j] = k_heads[(size_t)h * head_stride + j];
+    if (rotate) oref_fwht(x, d);
+    float sh = oref_sumsq_tree(x, d);
+    s = (h == 0) ? sh : s + sh;
+  }
+  return oref_round_dtype(sqrtf(s), meta_dtype);
+}
+
+/* Key transform of one head vector with a norm that was computed elsewhere (nf, already
+ * rounded to the metadata type): u = fp16(K_h / nf). */
+void oref_key_transform_given_norm(const float *k, int d, int rotate, float nf, float *u) {
+  float x[1024];
+  for (int j = 0; j < d; ++j) x[j] = k[j];
+  if (rotate) oref_fwht(x, d);
+  float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
+  for (int j = 0; j < d; ++j) u[j] = oref_round_f16(x[j] * inv);
 }
 
 /* Query transform [Key-xf]: Q_h = H(Q)/sqrt(D), no normalization. */
@@ -297,7 +335,8 @@ static void quantize_block(const stream_view *s, int pos) {
  *               as in OScaR-Inference where attention precedes BufferQuant)
  *               and is flushed at the start of the next append. */
 static void stream_append(const stream_view *s, const float *k, const float *v, int n,
-                          size_t row_stride, int eager, int *np, int *nr) {
+                          size_t row_stride, const float *tok_norm, int eager, int *np,
+                          int *nr) {
   const oref_cache *c = s->c;
   int d = c->d, R = c->R;
   for (int t = 0; t < n; ++t) {
@@ -306,8 +345,14 @@ static void stream_append(const stream_view *s, const float *k, const float *v, 
       *np += R;
       *nr = 0;
     }
-    oref_key_transform(k + (size_t)t * row_stride, d, c->rotate, c->scale_mode,
-                       c->meta_dtype, s->res_k + (size_t)(*nr) * d, &s->res_norm[*nr]);
+    if (tok_norm) {              /* one norm per token over all kv heads [Fused-HN] */
+      oref_key_transform_given_norm(k + (size_t)t * row_stride, d, c->rotate, tok_norm[t],
+                                    s->res_k + (size_t)(*nr) * d);
+      s->res_norm[*nr] = tok_norm[t];
+    } else {
+      oref_key_transform(k + (size_t)t * row_stride, d, c->rotate, c->scale_mode,
+                         c->meta_dtype, s->res_k + (size_t)(*nr) * d, &s->res_norm[*nr]);
+    }
     for (int j = 0; j < d; ++j) s->res_v[(size_t)(*nr) * d + j] = v[(size_t)t * row_stride + j];
     *nr += 1;
   }
@@ -328,6 +373,15 @@ int oref_append(oref_cache *c, const float *k, const float *v, int T,
     if (c->n_packed[b] + c->n_res[b] + n > c->cap_tokens) return -1;
   }
   int units = c->batch * c->n_kv_heads;
+  float *tok_norm = NULL;       /* [batch][T], only for the all-heads norm */
+  if (c->norm_scope == OREF_NORM_ALL_KV_HEADS && c->scale_mode == OREF_SCALE_L2) {
+    tok_norm = (float *)malloc(sizeof(float) * (size_t)c->batch * (size_t)(T > 0 ? T : 1));
+    for (int b = 0; b < c->batch; ++b)
+      for (int t = 0; t < (new_lens ? new_lens[b] : T); ++t)
+        tok_norm[(size_t)b * T + t] = oref_token_norm_all_heads(
+            k + ((size_t)b * T + t) * c->n_kv_heads * c->d, c->n_kv_heads, (size_t)c->d, c->d,
+            c->rotate, c->meta_dtype);
+  }
   int32_t *np_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)units);
   int32_t *nr_out = (int32_t *)malloc(sizeof(int32_t) * (size_t)units);
 #ifdef _OPENMP
@@ -341,7 +395,7 @@ int oref_append(oref_cache *c, const float *k, const float *v, int T,
     const float *kb = k + ((size_t)b * T * c->n_kv_heads + h) * c->d;
     const float *vb = v + ((size_t)b * T * c->n_kv_heads + h) * c->d;
     int np = c->n_packed[b], nr = c->n_res[b];
-    stream_append(&s, kb, vb, n, row, eager, &np, &nr);
+    stream_append(&s, kb, vb, n, row, tok_norm ? tok_norm + (size_t)b * T : NULL, eager, &np, &nr);
     np_out[u] = np;
     nr_out[u] = nr;
   }
@@ -351,6 +405,7 @@ int oref_append(oref_cache *c, const float *k, const float *v, int T,
   }
   free(np_out);
   free(nr_out);
+  free(tok_norm);
   return 0;
 }
 

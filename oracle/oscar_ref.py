@@ -16,6 +16,7 @@ import numpy as np
 F32, BF16, F16 = 0, 1, 2
 ZP_INT, ZP_MIN = 0, 1
 SCALE_NONE, SCALE_L2 = 0, 1
+NORM_PER_HEAD, NORM_ALL_KV_HEADS = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oscar_oracle.c")
@@ -36,7 +37,7 @@ def build_oracle(force: bool = False) -> str:
 class _CCache(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d", "bits", "k_group", "v_group", "R", "meta_dtype", "zp_mode", "rotate",
-        "scale_mode", "batch", "n_kv_heads", "cap_tokens")] + [
+        "scale_mode", "norm_scope", "batch", "n_kv_heads", "cap_tokens")] + [
         ("n_packed", C.c_void_p), ("n_res", C.c_void_p),
         ("k_codes", C.c_void_p), ("k_delta", C.c_void_p), ("k_zero", C.c_void_p),
         ("k_norm", C.c_void_p), ("v_codes", C.c_void_p), ("v_delta", C.c_void_p),
@@ -57,6 +58,9 @@ def lib():
         L.oref_sumsq_tree.argtypes = [fp, C.c_int]
         L.oref_key_transform.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, fp, fp]
         L.oref_query_transform.argtypes = [fp, C.c_int, C.c_int, fp]
+        L.oref_token_norm_all_heads.restype = C.c_float
+        L.oref_token_norm_all_heads.argtypes = [fp, C.c_int, C.c_size_t, C.c_int, C.c_int, C.c_int]
+        L.oref_key_transform_given_norm.argtypes = [fp, C.c_int, C.c_int, C.c_float, fp]
         L.oref_quant_params.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int, C.c_int, fp, fp]
         L.oref_quant_code.restype = C.c_uint8
         L.oref_quant_code.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int, C.c_int]
@@ -111,6 +115,20 @@ def key_transform(k, rotate=1, scale_mode=SCALE_L2, meta_dtype=F32):
     n = np.zeros(1, np.float32)
     lib().oref_key_transform(_fp(k), k.shape[0], rotate, scale_mode, meta_dtype, _fp(u), _fp(n))
     return u, float(n[0])
+
+
+def token_norm_all_heads(k_heads, rotate=1, meta_dtype=F32) -> float:
+    """k_heads: [n_kv_heads, d] of one token; the one norm over all its kv heads."""
+    k = _f32(k_heads)
+    return float(lib().oref_token_norm_all_heads(_fp(k), k.shape[0], k.shape[1], k.shape[1],
+                                                 rotate, meta_dtype))
+
+
+def key_transform_given_norm(k, nf, rotate=1):
+    k = _f32(k)
+    u = np.empty_like(k)
+    lib().oref_key_transform_given_norm(_fp(k), k.shape[0], rotate, C.c_float(nf), _fp(u))
+    return u
 
 
 def query_transform(q, rotate=1):
@@ -179,6 +197,7 @@ class OracleConfig:
     zp_mode: int = ZP_INT
     rotate: int = 1
     scale_mode: int = SCALE_L2
+    norm_scope: int = NORM_PER_HEAD
 
 
 class OracleCache:
@@ -205,6 +224,7 @@ class OracleCache:
         c.d, c.bits, c.k_group, c.v_group, c.R = d, cfg.bits, cfg.k_group, cfg.v_group, R
         c.meta_dtype, c.zp_mode, c.rotate, c.scale_mode = (cfg.meta_dtype, cfg.zp_mode,
                                                           cfg.rotate, cfg.scale_mode)
+        c.norm_scope = cfg.norm_scope
         c.batch, c.n_kv_heads, c.cap_tokens = B, H, cap_tokens
         for name in ("n_packed", "n_res", "k_codes", "k_delta", "k_zero", "k_norm", "v_codes",
                      "v_delta", "v_zero", "res_k", "res_v", "res_norm"):

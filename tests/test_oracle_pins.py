@@ -139,6 +139,83 @@ def test_zero_token_gives_zero_direction():
     assert n == 0.0 and not u.any()
 
 
+# ------------------------------------------- one norm over all kv heads --
+
+def test_all_heads_norm_is_the_norm_of_the_whole_token():
+    """App. "Fused Hadamard-Norm Kernel": the squared sums are accumulated across heads.  The
+    rotation is orthogonal per head, so the token-wise norm must equal the plain L2 norm of
+    the token's concatenated (un-rotated) head vectors; normalized heads then have squared
+    norms that sum to one, and n * K_u restores every head's rotated vector."""
+    rng = np.random.default_rng(5)
+    H = hadamard_closed_form(128)
+    for n_heads in (1, 2, 8):
+        for _ in range(5):
+            k = (rng.standard_normal((n_heads, 128)) * rng.lognormal(0, 1, (n_heads, 1))).astype(np.float32)
+            k[0, 5] *= 12
+            n = oracle.token_norm_all_heads(k, meta_dtype=F32)
+            want = np.linalg.norm(k.astype(np.float64))
+            assert abs(n - want) <= 1e-6 * want
+            n16 = oracle.token_norm_all_heads(k, meta_dtype=F16)
+            assert n16 == float(np.float16(n16)) and abs(n16 - want) <= 2.0 ** -11 * want * 1.01
+            tot = 0.0
+            for h in range(n_heads):
+                u = oracle.key_transform_given_norm(k[h], n16)
+                assert np.array_equal(u, u.astype(np.float16).astype(np.float32))
+                kh = H @ k[h].astype(np.float64)
+                assert np.abs(u.astype(np.float64) * n16 - kh).max() <= n16 * 2.0 ** -12 * 1.05 + 1e-6 * n16
+                tot += float((u.astype(np.float64) ** 2).sum())
+            assert abs(tot - 1.0) < 4e-3
+    # with one head the two scopes are the same function
+    k = rng.standard_normal(128).astype(np.float32)
+    u1, n1 = oracle.key_transform(k, meta_dtype=F16)
+    n2 = oracle.token_norm_all_heads(k[None], meta_dtype=F16)
+    assert n1 == n2 and np.array_equal(u1, oracle.key_transform_given_norm(k, n2))
+
+
+def test_all_heads_norm_in_the_cache():
+    """Cache-level behaviour of the all-heads scope: every head of a token stores the same norm,
+    that norm is the whole token's L2 norm, bulk and token-by-token ingestion agree, values are
+    untouched, a single-head cache is identical under both scopes, and with 8-bit codes the
+    decode still reproduces full-precision attention (the norm cancels: n * K_u = K_h)."""
+    w = synth.TINY.replace(n_kv_heads=2, n_q_heads=4)
+    k, v = synth.make_kv_batch(w, 0, 300)
+    cfg = OracleConfig(128, 2, 128, 32, 128, F16, norm_scope=oracle.NORM_ALL_KV_HEADS)
+    a = OracleCache(cfg, k.shape[0], 2, 512)
+    a.append(k, v, eager=True)
+    assert np.array_equal(a.k_norm[:, 0], a.k_norm[:, 1]) and np.array_equal(a.res_norm[:, 0], a.res_norm[:, 1])
+    npk, nr = int(a.n_packed[0]), int(a.n_res[0])
+    want = np.linalg.norm(k.astype(np.float64).reshape(k.shape[0], k.shape[1], -1), axis=-1)
+    got = np.concatenate([a.k_norm[:, 0, :npk], a.res_norm[:, 0, :nr]], axis=1)
+    assert np.abs(got - want).max() <= 2.0 ** -11 * want.max() * 1.01
+    b = OracleCache(cfg, k.shape[0], 2, 512)
+    for s in (1, 127, 1, 100, 71):
+        pos = int(b.n_packed[0] + b.n_res[0])
+        b.append(k[:, pos:pos + s], v[:, pos:pos + s])
+    b.append(k[:, :0], v[:, :0], eager=True)
+    for name in ("n_packed", "n_res", "k_codes", "k_delta", "k_zero", "k_norm", "v_codes", "v_delta", "v_zero"):
+        assert np.array_equal(getattr(a, name), getattr(b, name)), name
+    p = OracleCache(OracleConfig(128, 2, 128, 32, 128, F16), k.shape[0], 2, 512)
+    p.append(k, v, eager=True)
+    assert np.array_equal(p.v_codes, a.v_codes) and np.array_equal(p.v_delta, a.v_delta)
+    assert not np.array_equal(p.k_norm, a.k_norm)
+    # one head: scopes coincide bit for bit
+    k1, v1 = k[:, :, :1], v[:, :, :1]
+    c0 = OracleCache(OracleConfig(128, 2, 128, 32, 128, F16), k.shape[0], 1, 512)
+    c1 = OracleCache(cfg, k.shape[0], 1, 512)
+    c0.append(k1, v1, eager=True)
+    c1.append(k1, v1, eager=True)
+    for name in ("k_codes", "k_delta", "k_zero", "k_norm", "res_k", "res_norm"):
+        assert np.array_equal(getattr(c0, name), getattr(c1, name)), name
+    # 8-bit: decode equals full-precision attention on the original K, V
+    cfg8 = OracleConfig(128, 8, 128, 32, 128, F32, norm_scope=oracle.NORM_ALL_KV_HEADS)
+    c8 = OracleCache(cfg8, k.shape[0], 2, 512)
+    c8.append(k, v, eager=True)
+    q = synth.make_q(w)
+    out = c8.decode_attn(q)
+    ref = full_precision_attention(q, k, v, 2)
+    assert np.linalg.norm(out - ref) / np.linalg.norm(ref) < 2e-2
+
+
 # --------------------------------------------------------------- quantizer --
 
 @pytest.mark.parametrize("bits", [2, 4, 8])

@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--context", type=int, default=0, help="override the context length (multiple of 128)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size")
     ap.add_argument("--copies", type=int, default=0, help="override the number of cache copies")
+    ap.add_argument("--norm-all-heads", action="store_true",
+                    help="token norm over all kv heads instead of per (token, kv head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
     ap.add_argument("--bf16-splits", type=int, default=0, help="override the comparator's split-K factor")
@@ -74,7 +76,8 @@ def cpu_baseline(w, kd, vd, q_host, ob_cfg, budget_s=12.0):
     v = vd[:nb].float().cpu().numpy()
     meta = {"f16": oracle.F16, "f32": oracle.F32}[w.meta_dtype]
     cache = oracle.OracleCache(oracle.OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group,
-                                                   w.page_size, meta), nb, w.n_kv_heads,
+                                                   w.page_size, meta, norm_scope=ob_cfg.norm_scope),
+                               nb, w.n_kv_heads,
                                (w.context // w.page_size + 2) * w.page_size)
     t0 = time.perf_counter()
     cache.append(k, v, eager=True, nthreads=threads)
@@ -142,7 +145,8 @@ def measure(args, w, np, torch, ob, synth):
     io = {"f32": ob.F32, "bf16": ob.BF16, "f16": ob.F16}[w.io_dtype]
     meta = {"f32": ob.F32, "f16": ob.F16}[w.meta_dtype]
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
-                    w.page_size, io, meta)
+                    w.page_size, io, meta,
+                    norm_scope=ob.NORM_ALL_KV_HEADS if args.norm_all_heads else ob.NORM_PER_HEAD)
     R = w.page_size
     total_steps = args.steps + args.warmup
     pages = (w.context + total_steps) // R + 2
@@ -324,7 +328,8 @@ def measure(args, w, np, torch, ob, synth):
                    "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "context": w.context,
                    "bits": w.bits, "k_group": w.k_group, "v_group": w.v_group,
                    "io_dtype": w.io_dtype,
-                   "step": "append 1 token/seq (1 launch) + decode attention (partial + reduce launches)",
+                   "norm_scope": "all kv heads" if args.norm_all_heads else "per kv head",
+        "step": "append 1 token/seq (1 launch) + decode attention (partial + reduce launches)",
                    "splits": splits, "cache_copies_rotated": n_copies},
         "roofline": {"bound": "hbm",
                      "kernel": ("oscar_decode_mfma_kernel" if w.meta_dtype == "f16" and

@@ -46,7 +46,10 @@ extern "C" {
 enum { OSCAR_F32 = 0, OSCAR_BF16 = 1, OSCAR_F16 = 2 };
 /* zero-point form: integer z = round(-min/Delta) (Eq. 3-4) or float zero = min */
 enum { OSCAR_ZP_INT = 0, OSCAR_ZP_MIN = 1 };
-/* scope of the token norm: one norm per (token, kv head), or one per token over all kv heads */
+/* scope of the token norm: one norm per (token, kv head) (App. "Overall Design": n_k is the
+ * norm of the head's vector), or one per token from the squared sums of all kv heads (App.
+ * "Fused Hadamard-Norm Kernel"); the cache layout is the same, every head's norm slot of a
+ * token then holds the same value */
 enum { OSCAR_NORM_PER_HEAD = 0, OSCAR_NORM_ALL_KV_HEADS = 1 };
 /* status codes */
 enum {
@@ -65,7 +68,7 @@ enum {
 /* Parameters of the method (Algorithm "The OScaR algorithm": G, R, d_h; Eq. 3-4: b).
  * Checked on every call. Built: head_dim 128; bits 2|4; k_group 32|64|128;
  * v_group 32|64|128; page_size 128; io_dtype any; meta_dtype F16|F32;
- * zp_mode OSCAR_ZP_INT|OSCAR_ZP_MIN; norm_scope OSCAR_NORM_PER_HEAD; n_q_heads/n_kv_heads <= 8.
+ * zp_mode OSCAR_ZP_INT|OSCAR_ZP_MIN; norm_scope either; n_q_heads/n_kv_heads <= 8.
  * Anything else returns OSCAR_ERR_UNSUPPORTED. */
 typedef struct oscar_config {
   int32_t head_dim;    /* d_h */

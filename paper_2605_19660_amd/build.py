@@ -19,6 +19,7 @@ COMMON = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
 SOURCES = {
     "oscar_api.hip": [],
     "oscar_quantize.hip": ["-ffp-contract=off"],
+    "oscar_quantize_allheads.hip": ["-ffp-contract=off"],
     "oscar_decode.hip": [],
     "oscar_decode_mfma.hip": [],
     "oscar_bf16_decode.hip": [],
@@ -42,7 +43,7 @@ def _compile(name: str, extra: list[str], verbose: bool) -> str:
     return obj
 
 
-def build(verbose: bool = False, jobs: int = 4) -> str:
+def build(verbose: bool = False, jobs: int = 6) -> str:
     os.makedirs(OBJ, exist_ok=True)
     present = {n: e for n, e in SOURCES.items() if os.path.exists(os.path.join(CSRC, n))}
     with ThreadPoolExecutor(max_workers=jobs) as ex:

@@ -28,7 +28,6 @@ int oscar_validate_config(const oscar_config* cfg) {
   if (cfg->k_group != 32 && cfg->k_group != 64 && cfg->k_group != 128) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->v_group != 32 && cfg->v_group != 64 && cfg->v_group != 128) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->meta_dtype == OSCAR_BF16) return OSCAR_ERR_UNSUPPORTED;
-  if (cfg->norm_scope != OSCAR_NORM_PER_HEAD) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->n_q_heads / cfg->n_kv_heads > OSCAR_MAX_GQA) return OSCAR_ERR_UNSUPPORTED;
   return OSCAR_OK;
 }

@@ -33,14 +33,15 @@ def to_dev(x, io):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dt).contiguous()
 
 
-def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True, zp_mode=0):
+def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True, zp_mode=0, norm_scope=0):
     ob = _ob()
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
-                    w.page_size, DT[w.io_dtype], DT[w.meta_dtype], zp_mode=zp_mode)
+                    w.page_size, DT[w.io_dtype], DT[w.meta_dtype], zp_mode=zp_mode,
+                    norm_scope=norm_scope)
     g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm, fused=fused)
     o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
-                                 DT[w.meta_dtype], zp_mode=zp_mode), w.batch, w.n_kv_heads,
-                    (cap_pages + 1) * w.page_size)
+                                 DT[w.meta_dtype], zp_mode=zp_mode, norm_scope=norm_scope),
+                    w.batch, w.n_kv_heads, (cap_pages + 1) * w.page_size)
     return g, o
 
 
@@ -334,6 +335,39 @@ def test_float_zero_point_mode_bitexact_and_decode(io, meta, bits, kg, vg, path,
         ob.quantize_append(g, to_dev(k[:, t:t + 1], io), to_dev(v[:, t:t + 1], io))
         o.append(k[:, t:t + 1], v[:, t:t + 1])
     assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
+@pytest.mark.parametrize("io,meta,bits,kg,n_kv,zp", [
+    ("bf16", "f16", 2, 128, 8, 0),
+    ("f16", "f16", 4, 32, 3, 0),       # a head count that is no multiple of the fetch width
+    ("f32", "f32", 2, 64, 1, 0),       # one head: the scope makes no difference
+    ("bf16", "f16", 2, 128, 5, 1),
+])
+def test_norm_over_all_kv_heads_bitexact_and_decode(io, meta, bits, kg, n_kv, zp):
+    """norm_scope = NORM_ALL_KV_HEADS (App. "Fused Hadamard-Norm Kernel"): one norm per token
+    from the squared sums of all kv heads.  Prefill (whole blocks), a mixed block (old residual
+    tokens + new ones), token-by-token appends with a deferred flush: cache bit-exact against
+    the oracle, every head of a token holding the same norm; decode within tolerance."""
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=2 * n_kv, n_kv_heads=n_kv, context=128 * 3 + 61,
+                                  io_dtype=io, meta_dtype=meta, bits=bits, k_group=kg)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8, zp_mode=zp, norm_scope=ob.NORM_ALL_KV_HEADS)
+    n0, n1 = 128 + 17, 128 * 2 + 99
+    ob.quantize_append(g, to_dev(k[:, :n0], io), to_dev(v[:, :n0], io), eager=True, max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    ob.quantize_append(g, to_dev(k[:, n0:n1], io), to_dev(v[:, n0:n1], io), eager=True)   # mixed block
+    o.append(k[:, n0:n1], v[:, n0:n1], eager=True)
+    for t in range(n1, w.context):      # crosses a page boundary: one deferred flush
+        ob.quantize_append(g, to_dev(k[:, t:t + 1], io), to_dev(v[:, t:t + 1], io))
+        o.append(k[:, t:t + 1], v[:, t:t + 1])
+    assert_cache_equal(g, o, w)
+    if n_kv > 1:
+        d0, d1 = ob.debug_dump(g, 1, 0), ob.debug_dump(g, 1, n_kv - 1)
+        assert np.array_equal(d0["k_norm"], d1["k_norm"]) and np.array_equal(d0["res_norm"], d1["res_norm"])
     out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
     assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
 

@@ -32,6 +32,9 @@
  *   [Flow]     same appendix, "Prefill and Decode Workflows" / "Residual
  *              Flush": residual keys are already normalized, flush only
  *              quantizes.
+ *   [Abl]      App. "Ablation Study": rotation and scaling switched off one at a
+ *              time; alternative scaling coefficients (maximum absolute value /
+ *              mean absolute value across the channels of a token).
  *   [Fused-HN] same appendix, "Fused Hadamard-Norm Kernel": all kv heads of a
  *              token are transformed, their squared sums accumulated across
  *              heads, one token-wise norm normalizes every head (the
@@ -49,6 +52,8 @@
  *   - max == min: Delta := |min| (1 if that is 0), so a constant group
  *     round-trips exactly.
  *   - zero-norm token: K_u = 0.
+ *   - mean absolute value: |x_j| summed in the same balanced tree as the squared
+ *     sum, times 1/d.
  *   - norm over all kv heads: the per-head squared sums (each in its tree
  *     order) are added in head order, then one sqrt; the same stored norm is
  *     kept with every head of the token.
@@ -69,7 +74,7 @@
 
 enum { OREF_F32 = 0, OREF_BF16 = 1, OREF_F16 = 2 };
 enum { OREF_ZP_INT = 0, OREF_ZP_MIN = 1 };
-enum { OREF_SCALE_NONE = 0, OREF_SCALE_L2 = 1 };
+enum { OREF_SCALE_NONE = 0, OREF_SCALE_L2 = 1, OREF_SCALE_MAX = 2, OREF_SCALE_MEAN_ABS = 3 };
 enum { OREF_NORM_PER_HEAD = 0, OREF_NORM_ALL_KV_HEADS = 1 };
 
 typedef struct {
@@ -82,7 +87,8 @@ typedef struct {
   int32_t meta_dtype; /* storage type of Delta, z, n: OREF_F32 or OREF_F16 */
   int32_t zp_mode;    /* OREF_ZP_INT = Eq.3-4 ; OREF_ZP_MIN = float zero-point (cost section of App. complexity) */
   int32_t rotate;     /* 1 = Canalized Rotation on (ablation switch) */
-  int32_t scale_mode; /* OREF_SCALE_L2 = Omni-Token Scaling on (ablation switch) */
+  int32_t scale_mode; /* OREF_SCALE_L2 = Omni-Token Scaling as in the method; NONE = off;
+                         MAX / MEAN_ABS = the alternative coefficients of [Abl] */
   int32_t norm_scope; /* OREF_NORM_PER_HEAD: n = ||K_h|| of one head's vector [Key-xf];
                          OREF_NORM_ALL_KV_HEADS: one n per token from the squared sums of all
                          kv heads (the fused preprocessing kernel's description, [Fused-HN]) */
@@ -161,20 +167,40 @@ float oref_sumsq_tree(const float *x, int d) {
   return t[0];
 }
 
+/* Sum of |x_j| in the same balanced tree. */
+float oref_sumabs_tree(const float *x, int d) {
+  float t[1024], s[1024];
+  for (int i = 0; i < d; ++i) t[i] = fabsf(x[i]);
+  for (int h = 1; h < d; h <<= 1) {
+    for (int i = 0; i < d; ++i) s[i] = t[i] + t[i ^ h];
+    memcpy(t, s, sizeof(float) * (size_t)d);
+  }
+  return t[0];
+}
+
 /* Key transform of one token of one head [Key-xf], [Alg.1: X_K <- FHT(X_K);
  * s_K <- ||X_K||_2; X_K <- X_K / s_K].
  * in : k[d]  (already exactly representable in the input dtype)
  * out: u[d]  = fp16(K_h / n_st),  *n_st = norm rounded to the metadata type.
- * Ablation switches: rotate=0 skips the Hadamard, scale_mode=NONE keeps n=1. */
+ * Ablation switches [Abl]: rotate=0 skips the Hadamard, scale_mode=NONE keeps n=1,
+ * MAX / MEAN_ABS replace the L2 norm by another per-token coefficient. */
 void oref_key_transform(const float *k, int d, int rotate, int scale_mode,
                         int meta_dtype, float *u, float *n_st) {
   float x[1024];
   for (int j = 0; j < d; ++j) x[j] = k[j];
   if (rotate) oref_fwht(x, d);
   float nf = 1.0f;
-  if (scale_mode == OREF_SCALE_L2) {
-    float s = oref_sumsq_tree(x, d);
-    float n = sqrtf(s);
+  if (scale_mode != OREF_SCALE_NONE) {
+    float n;
+    if (scale_mode == OREF_SCALE_L2) {
+      n = sqrtf(oref_sumsq_tree(x, d));
+    } else if (scale_mode == OREF_SCALE_MAX) {          /* [Abl] max_j |x_j| */
+      n = 0.0f;
+      for (int j = 0; j < d; ++j)
+        if (fabsf(x[j]) > n) n = fabsf(x[j]);
+    } else {                                            /* [Abl] mean_j |x_j| */
+      n = oref_sumabs_tree(x, d) * (1.0f / (float)d);
+    }
     nf = oref_round_dtype(n, meta_dtype);
     float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
     for (int j = 0; j < d; ++j) x[j] = x[j] * inv;

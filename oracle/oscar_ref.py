@@ -15,7 +15,7 @@ import numpy as np
 
 F32, BF16, F16 = 0, 1, 2
 ZP_INT, ZP_MIN = 0, 1
-SCALE_NONE, SCALE_L2 = 0, 1
+SCALE_NONE, SCALE_L2, SCALE_MAX, SCALE_MEAN_ABS = 0, 1, 2, 3
 NORM_PER_HEAD, NORM_ALL_KV_HEADS = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

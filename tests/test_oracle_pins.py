@@ -8,7 +8,8 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import F16, F32, BF16, ZP_INT, ZP_MIN, SCALE_L2, SCALE_NONE, OracleCache, OracleConfig
+from oracle import (F16, F32, BF16, ZP_INT, ZP_MIN, SCALE_L2, SCALE_NONE, SCALE_MAX, SCALE_MEAN_ABS,
+                    OracleCache, OracleConfig)
 from paper_2605_19660_amd import synth
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -137,6 +138,52 @@ def test_key_transform_unit_norm_and_restoration(meta):
 def test_zero_token_gives_zero_direction():
     u, n = oracle.key_transform(np.zeros(128, np.float32), meta_dtype=F16)
     assert n == 0.0 and not u.any()
+
+
+# ---------------------------------- alternative scaling coefficients --
+
+@pytest.mark.parametrize("rotate", [0, 1])
+def test_alternative_scaling_coefficients(rotate):
+    """App. "Ablation Study": the coefficient can be the maximum or the mean absolute value over
+    the token's channels instead of the L2 norm.  Closed forms on the (rotated) vector: n equals
+    max|x| exactly / mean|x| to fp32 accuracy; K_u = x / n, so max|K_u| = 1 exactly resp.
+    mean|K_u| = 1; n * K_u restores x; scaling the token by a power of two scales n alone."""
+    rng = np.random.default_rng(21)
+    H = hadamard_closed_form(128) if rotate else np.eye(128)
+    for _ in range(8):
+        k = (rng.standard_normal(128) * rng.lognormal(0, 1)).astype(np.float32)
+        k[9] *= 15
+        x = H @ k.astype(np.float64)
+        u, n = oracle.key_transform(k, rotate=rotate, scale_mode=SCALE_MAX, meta_dtype=F32)
+        assert abs(n - np.abs(x).max()) <= 2e-6 * n
+        assert np.abs(u).max() == 1.0
+        assert np.abs(u.astype(np.float64) * n - x).max() <= n * 2.0 ** -12 * 1.05 + 1e-6 * n
+        u2, n2 = oracle.key_transform(4 * k, rotate=rotate, scale_mode=SCALE_MAX, meta_dtype=F32)
+        assert n2 == 4 * n and np.array_equal(u, u2)
+        u, n = oracle.key_transform(k, rotate=rotate, scale_mode=SCALE_MEAN_ABS, meta_dtype=F32)
+        assert abs(n - np.abs(x).mean()) <= 2e-6 * n
+        assert abs(np.abs(u.astype(np.float64)).mean() - 1.0) < 2e-3
+        assert np.abs(u.astype(np.float64) * n - x).max() <= np.abs(x).max() * 2.0 ** -11 * 1.05 + 1e-6 * n
+        u, n = oracle.key_transform(k, rotate=rotate, scale_mode=SCALE_NONE, meta_dtype=F16)
+        assert n == 1.0 and np.abs(u.astype(np.float64) - x).max() <= np.abs(x).max() * 2.0 ** -11 * 1.05
+    # without rotation and scaling the transform is the fp16 rounding of the input
+    k = rng.standard_normal(128).astype(np.float32)
+    u, n = oracle.key_transform(k, rotate=0, scale_mode=SCALE_NONE)
+    assert n == 1.0 and np.array_equal(u, k.astype(np.float16).astype(np.float32))
+
+
+@pytest.mark.parametrize("rotate,scale", [(0, SCALE_NONE), (0, SCALE_L2), (1, SCALE_NONE), (1, SCALE_MAX),
+                                          (1, SCALE_MEAN_ABS), (0, SCALE_MEAN_ABS)])
+def test_every_ablation_decodes_to_full_precision_attention_at_8_bits(rotate, scale):
+    """Whatever the switches, n * K_u is the (rotated) key and Q is rotated alike, so with 8-bit
+    codes the decode must reproduce plain attention on the original K, V."""
+    w = synth.TINY.replace(n_kv_heads=2, n_q_heads=4, context=300)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    c = OracleCache(OracleConfig(128, 8, 128, 32, 128, F32, ZP_INT, rotate, scale), k.shape[0], 2, 512)
+    c.append(k, v, eager=True)
+    ref = full_precision_attention(q, k, v, 2)
+    assert np.linalg.norm(c.decode_attn(q) - ref) / np.linalg.norm(ref) < 3e-2
 
 
 # ------------------------------------------- one norm over all kv heads --

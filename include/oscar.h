@@ -51,6 +51,11 @@ enum { OSCAR_ZP_INT = 0, OSCAR_ZP_MIN = 1 };
  * "Fused Hadamard-Norm Kernel"); the cache layout is the same, every head's norm slot of a
  * token then holds the same value */
 enum { OSCAR_NORM_PER_HEAD = 0, OSCAR_NORM_ALL_KV_HEADS = 1 };
+/* ablation switches (App. "Ablation Study"); 0 everywhere = the method as published */
+enum { OSCAR_ROTATION_ON = 0, OSCAR_ROTATION_OFF = 1 }; /* OFF: no Hadamard on K nor on Q */
+/* per-token scaling coefficient n: L2 norm; none (n = 1); maximum absolute value over the
+ * token's channels; mean absolute value over them */
+enum { OSCAR_SCALE_L2 = 0, OSCAR_SCALE_NONE = 1, OSCAR_SCALE_MAX = 2, OSCAR_SCALE_MEAN_ABS = 3 };
 /* status codes */
 enum {
   OSCAR_OK = 0,
@@ -68,7 +73,8 @@ enum {
 /* Parameters of the method (Algorithm "The OScaR algorithm": G, R, d_h; Eq. 3-4: b).
  * Checked on every call. Built: head_dim 128; bits 2|4; k_group 32|64|128;
  * v_group 32|64|128; page_size 128; io_dtype any; meta_dtype F16|F32;
- * zp_mode OSCAR_ZP_INT|OSCAR_ZP_MIN; norm_scope either; n_q_heads/n_kv_heads <= 8.
+ * zp_mode OSCAR_ZP_INT|OSCAR_ZP_MIN; norm_scope either; rotation either; scale_mode any;
+ * n_q_heads/n_kv_heads <= 8.
  * Anything else returns OSCAR_ERR_UNSUPPORTED. */
 typedef struct oscar_config {
   int32_t head_dim;    /* d_h */
@@ -82,6 +88,8 @@ typedef struct oscar_config {
   int32_t meta_dtype;  /* storage type of Delta, zero-point and token norm */
   int32_t zp_mode;
   int32_t norm_scope;
+  int32_t rotation;    /* OSCAR_ROTATION_ON | OSCAR_ROTATION_OFF */
+  int32_t scale_mode;  /* OSCAR_SCALE_*; anything but L2 needs OSCAR_NORM_PER_HEAD */
 } oscar_config;
 
 /* The paged cache. Plain data; every pointer is DEVICE memory the caller

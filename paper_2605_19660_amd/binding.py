@@ -15,6 +15,8 @@ import numpy as np
 F32, BF16, F16 = 0, 1, 2
 ZP_INT, ZP_MIN = 0, 1
 NORM_PER_HEAD, NORM_ALL_KV_HEADS = 0, 1
+ROTATION_ON, ROTATION_OFF = 0, 1
+SCALE_L2, SCALE_NONE, SCALE_MAX, SCALE_MEAN_ABS = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5
 APPEND_EAGER = 1
 
@@ -39,7 +41,7 @@ class OscarError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "head_dim", "n_q_heads", "n_kv_heads", "bits", "k_group", "v_group", "page_size",
-        "io_dtype", "meta_dtype", "zp_mode", "norm_scope")]
+        "io_dtype", "meta_dtype", "zp_mode", "norm_scope", "rotation", "scale_mode")]
 
 
 class CCache(C.Structure):
@@ -131,11 +133,13 @@ class Config:
     meta_dtype: int = F16
     zp_mode: int = ZP_INT
     norm_scope: int = NORM_PER_HEAD
+    rotation: int = ROTATION_ON
+    scale_mode: int = SCALE_L2
 
     def c(self) -> CConfig:
         return CConfig(self.head_dim, self.n_q_heads, self.n_kv_heads, self.bits, self.k_group,
                        self.v_group, self.page_size, self.io_dtype, self.meta_dtype, self.zp_mode,
-                       self.norm_scope)
+                       self.norm_scope, self.rotation, self.scale_mode)
 
 
 def torch_dtype(code: int):

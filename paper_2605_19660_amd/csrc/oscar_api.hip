@@ -22,12 +22,18 @@ int oscar_validate_config(const oscar_config* cfg) {
   if (cfg->zp_mode != OSCAR_ZP_INT && cfg->zp_mode != OSCAR_ZP_MIN) return OSCAR_ERR_INVALID_ARG;
   if (cfg->norm_scope != OSCAR_NORM_PER_HEAD && cfg->norm_scope != OSCAR_NORM_ALL_KV_HEADS)
     return OSCAR_ERR_INVALID_ARG;
+  if (cfg->rotation != OSCAR_ROTATION_ON && cfg->rotation != OSCAR_ROTATION_OFF)
+    return OSCAR_ERR_INVALID_ARG;
+  if (cfg->scale_mode < OSCAR_SCALE_L2 || cfg->scale_mode > OSCAR_SCALE_MEAN_ABS)
+    return OSCAR_ERR_INVALID_ARG;
   // what is built
   if (cfg->head_dim != OSCAR_D || cfg->page_size != OSCAR_R) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->bits != 2 && cfg->bits != 4) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->k_group != 32 && cfg->k_group != 64 && cfg->k_group != 128) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->v_group != 32 && cfg->v_group != 64 && cfg->v_group != 128) return OSCAR_ERR_UNSUPPORTED;
   if (cfg->meta_dtype == OSCAR_BF16) return OSCAR_ERR_UNSUPPORTED;
+  if (cfg->norm_scope == OSCAR_NORM_ALL_KV_HEADS && cfg->scale_mode != OSCAR_SCALE_L2)
+    return OSCAR_ERR_UNSUPPORTED;
   if (cfg->n_q_heads / cfg->n_kv_heads > OSCAR_MAX_GQA) return OSCAR_ERR_UNSUPPORTED;
   return OSCAR_OK;
 }

@@ -147,13 +147,57 @@ __device__ __forceinline__ float row_sumsq(const float (&x)[8]) {
   return s;
 }
 
+// the same tree over |x|, and the maximum of |x| (App. "Ablation Study": alternative
+// scaling coefficients)
+__device__ __forceinline__ float row_sumabs(const float (&x)[8]) {
+  float t[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t[i] = fabsf(x[i]);
+  float s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+  s = s + partner<0>(s);
+  s = s + partner<1>(s);
+  s = s + partner<2>(s);
+  s = s + partner<3>(s);
+  return s;
+}
+__device__ __forceinline__ float row_maxabs(const float (&x)[8]) {
+  float m = fabsf(x[0]);
+#pragma unroll
+  for (int i = 1; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
+  m = fmaxf(m, partner<0>(m));
+  m = fmaxf(m, partner<1>(m));
+  m = fmaxf(m, partner<2>(m));
+  m = fmaxf(m, partner<3>(m));
+  return m;
+}
+
+// The switches of the key transform (uniform over a launch): rotation on/off and the
+// OSCAR_SCALE_* coefficient.  Default-constructed = the method as published.
+struct KeyXf {
+  bool rotate = true;
+  int scale_mode = OSCAR_SCALE_L2;
+};
+__device__ __forceinline__ KeyXf key_xf_of(const oscar_config& cfg) {
+  KeyXf m;
+  m.rotate = cfg.rotation == OSCAR_ROTATION_ON;
+  m.scale_mode = cfg.scale_mode;
+  return m;
+}
+
 template <typename META>
 __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&sgn)[4],
-                                                float& n_st) {
-  rotate8(x, sgn);
-  const float s = row_sumsq(x);
-  float n = sqrtf(s);
-  float nf = round_meta<META>(n);
+                                                float& n_st, const KeyXf m = KeyXf()) {
+  if (m.rotate) rotate8(x, sgn);
+  float nf;
+  if (m.scale_mode == OSCAR_SCALE_L2) {
+    nf = round_meta<META>(sqrtf(row_sumsq(x)));
+  } else if (m.scale_mode == OSCAR_SCALE_MAX) {
+    nf = round_meta<META>(row_maxabs(x));
+  } else if (m.scale_mode == OSCAR_SCALE_MEAN_ABS) {
+    nf = round_meta<META>(row_sumabs(x) * (1.0f / (float)D));
+  } else {
+    nf = 1.0f;
+  }
   float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
   uint32_t w[4];
 #pragma unroll
@@ -165,8 +209,8 @@ __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&
 
 // Same transform with a norm that is already known (rounded to its storage type).
 __device__ __forceinline__ uint4 key_transform8_given(float (&x)[8], const uint32_t (&sgn)[4],
-                                                      float nf) {
-  rotate8(x, sgn);
+                                                      float nf, bool rotate) {
+  if (rotate) rotate8(x, sgn);
   float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
   uint32_t w[4];
 #pragma unroll
@@ -182,7 +226,7 @@ __device__ __forceinline__ uint4 key_transform8_given(float (&x)[8], const uint3
 // Heads are fetched four at a time; slots past the last head repeat it and add +0.
 template <typename IO, typename META>
 __device__ __forceinline__ float token_norm_all_heads(const IO* row0, int n_heads,
-                                                      const uint32_t (&sgn)[4]) {
+                                                      const uint32_t (&sgn)[4], bool rotate) {
   float s = 0.0f;
   for (int h0 = 0; h0 < n_heads; h0 += 4) {
     Raw8<IO> r[4];
@@ -195,7 +239,7 @@ __device__ __forceinline__ float token_norm_all_heads(const IO* row0, int n_head
     for (int j = 0; j < 4; ++j) {
       float x[8];
       r[j].widen(x);
-      rotate8(x, sgn);
+      if (rotate) rotate8(x, sgn);
       const float sh = row_sumsq(x);
       s = s + (h0 + j < n_heads ? sh : 0.0f);
     }
@@ -334,6 +378,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   const int cg = channel_group_of_row_lane(tid & 15);   // channels 8*cg .. 8*cg+7
   const int Hkv = P.c.cfg.n_kv_heads;
   const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
+  const KeyXf xf = key_xf_of(P.c.cfg);
   uint32_t sgn[4];
 #pragma unroll
   for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
@@ -388,14 +433,14 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       for (int p = 0; p < 8; ++p) {
         float x[8];
         kraw[p].widen(x);
-        ku[p] = key_transform8_given(x, sgn, nrm[p]);
+        ku[p] = key_transform8_given(x, sgn, nrm[p], xf.rotate);
       }
     } else {
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         float x[8];
         kraw[p].widen(x);
-        ku[p] = key_transform8<META>(x, sgn, nrm[p]);
+        ku[p] = key_transform8<META>(x, sgn, nrm[p], xf);
       }
     }
   } else if (do_block) {
@@ -426,9 +471,9 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       uint4 nu;
       if (NORM_ALL) {   // (rows that came from the residual drop the result)
         nn = to_f32<META>(pre_norm[tok_meta_pos(p * 16 + slot)]);
-        nu = key_transform8_given(x, sgn, nn);
+        nu = key_transform8_given(x, sgn, nn, xf.rotate);
       } else {
-        nu = key_transform8<META>(x, sgn, nn);
+        nu = key_transform8<META>(x, sgn, nn, xf);
       }
       ku[p].x = old ? kraw[p].a.x : nu.x;
       ku[p].y = old ? kraw[p].a.y : nu.y;
@@ -455,10 +500,10 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       kin.widen(x);
       uint4 nu;
       if (NORM_ALL) {
-        nn = token_norm_all_heads<IO, META>(knew + off - (size_t)kvh * D, Hkv, sgn);
-        nu = key_transform8_given(x, sgn, nn);
+        nn = token_norm_all_heads<IO, META>(knew + off - (size_t)kvh * D, Hkv, sgn, xf.rotate);
+        nu = key_transform8_given(x, sgn, nn, xf.rotate);
       } else {
-        nu = key_transform8<META>(x, sgn, nn);
+        nu = key_transform8<META>(x, sgn, nn, xf);
       }
       if (i < cnt) {
         const int ds = dst0 + i;
@@ -772,7 +817,8 @@ __global__ __launch_bounds__(256) void oscar_token_norm_kernel(AppendParams P) {
   const int tc = ti < n_paged ? ti : n_paged - 1;   // whole rows stay active for the exchanges
   const IO* knew = reinterpret_cast<const IO*>(P.k);
   const float nf = token_norm_all_heads<IO, META>(
-      knew + (((size_t)b * P.T + (size_t)tc) * Hkv) * D + cg * 8, Hkv, sgn);
+      knew + (((size_t)b * P.T + (size_t)tc) * Hkv) * D + cg * 8, Hkv, sgn,
+      P.c.cfg.rotation == OSCAR_ROTATION_ON);
   if (ti < n_paged) {
     const int pi = sp.r0 + ti;
     const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + sp.packed_pages + pi / R];

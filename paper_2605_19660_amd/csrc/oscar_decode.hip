@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void oscar_decode_partial_kernel(DecodeParams 
   const bool any_work = (pg0 < pg1) || has_res;
   if (any_work) {
     rotate_queries(s_q, P.q, ((size_t)b * Hq + (size_t)kvh * GQ) * D, P.c.cfg.io_dtype,
-                   P.qk_scale_log2, tid, GQ);
+                   P.qk_scale_log2, tid, GQ, P.c.cfg.rotation == OSCAR_ROTATION_ON);
   } else {
     __syncthreads();
   }

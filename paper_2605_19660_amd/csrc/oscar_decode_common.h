@@ -49,10 +49,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // Q_h = H(q)/sqrt(128) for gq heads in LDS, times scale*log2(e).  Whole workgroup (256).
+// rotate = false (ablation: Canalized Rotation off) leaves the queries un-rotated.
 __device__ __forceinline__ void rotate_queries(float (*s_q)[D], const void* q, size_t q_base,
-                                               int io_dtype, float mul, int tid, int gq) {
+                                               int io_dtype, float mul, int tid, int gq,
+                                               bool rotate) {
   for (int i = tid; i < gq * D; i += 256) s_q[i / D][i % D] = load_io(q, q_base + i, io_dtype);
   __syncthreads();
+  if (!rotate) {
+    for (int i = tid; i < gq * D; i += 256) s_q[i / D][i % D] *= mul;
+    __syncthreads();
+    return;
+  }
   for (int h = 1; h < D; h <<= 1) {
     for (int i = tid; i < gq * (D / 2); i += 256) {
       const int head = i / (D / 2), pr = i % (D / 2);

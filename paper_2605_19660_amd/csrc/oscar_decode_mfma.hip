@@ -456,7 +456,7 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
 #pragma unroll
   for (int s = 0; s < HP; ++s) {
     qraw[s].widen(qh[s], P.c.cfg.io_dtype);
-    rotate8(qh[s], sgn);
+    if (P.c.cfg.rotation == OSCAR_ROTATION_ON) rotate8(qh[s], sgn);
 #pragma unroll
     for (int i = 0; i < 8; ++i) qh[s][i] *= P.qk_scale_log2;
   }
@@ -854,12 +854,16 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipE
 }  // namespace
 
 // Launches the matrix-core partial pass when the configuration is one it is built for
-// (fp16 metadata; group sizes (128,32), (32,32) or (128,128)); OSCAR_ERR_UNSUPPORTED
+// (fp16 metadata; group sizes (128,32), (32,32) or (128,128); keys scaled into [-1, 1]); OSCAR_ERR_UNSUPPORTED
 // tells the caller to use the generic kernel.
 int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
                              hipEvent_t e0, hipEvent_t e1) {
   const DecodeParams& P = *reinterpret_cast<const DecodeParams*>(params);
   if (P.c.cfg.meta_dtype != OSCAR_F16) return OSCAR_ERR_UNSUPPORTED;
+  // the key operand's fixed exponent assumes Delta_k <= 1, which holds when |K_u| <= 1 (L2 or
+  // maximum scaling); the un-scaled and mean-absolute-value ablations go to the generic kernel
+  if (P.c.cfg.scale_mode != OSCAR_SCALE_L2 && P.c.cfg.scale_mode != OSCAR_SCALE_MAX)
+    return OSCAR_ERR_UNSUPPORTED;
   const char* force = getenv("OSCAR_DECODE_PATH");
   if (force && force[0] == 'g') return OSCAR_ERR_UNSUPPORTED;  // "generic"
   if (P.g.bits == 2)

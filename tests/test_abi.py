@@ -51,6 +51,9 @@ def test_cache_sizes_match_the_format():
     (dict(k_group=48), ob.ERR_INVALID_ARG),
     (dict(k_group=16), ob.ERR_UNSUPPORTED),
     (dict(norm_scope=5), ob.ERR_INVALID_ARG),
+    (dict(rotation=2), ob.ERR_INVALID_ARG),
+    (dict(scale_mode=4), ob.ERR_INVALID_ARG),
+    (dict(norm_scope=ob.NORM_ALL_KV_HEADS, scale_mode=ob.SCALE_MAX), ob.ERR_UNSUPPORTED),
     (dict(n_q_heads=30), ob.ERR_INVALID_ARG),
     (dict(n_q_heads=128), ob.ERR_UNSUPPORTED),
     (dict(io_dtype=7), ob.ERR_INVALID_ARG),

@@ -33,14 +33,20 @@ def to_dev(x, io):
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(dt).contiguous()
 
 
-def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True, zp_mode=0, norm_scope=0):
+def make_pair(w: synth.Workload, cap_pages, page_perm=None, fused=True, zp_mode=0, norm_scope=0,
+              rotation_off=False, scale="l2"):
     ob = _ob()
+    import oracle as orc
+    g_scale = {"l2": ob.SCALE_L2, "none": ob.SCALE_NONE, "max": ob.SCALE_MAX, "mean_abs": ob.SCALE_MEAN_ABS}[scale]
+    o_scale = {"l2": orc.SCALE_L2, "none": orc.SCALE_NONE, "max": orc.SCALE_MAX, "mean_abs": orc.SCALE_MEAN_ABS}[scale]
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
                     w.page_size, DT[w.io_dtype], DT[w.meta_dtype], zp_mode=zp_mode,
-                    norm_scope=norm_scope)
+                    norm_scope=norm_scope, rotation=ob.ROTATION_OFF if rotation_off else ob.ROTATION_ON,
+                    scale_mode=g_scale)
     g = ob.Cache(cfg, w.batch, cap_pages, page_perm=page_perm, fused=fused)
     o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
-                                 DT[w.meta_dtype], zp_mode=zp_mode, norm_scope=norm_scope),
+                                 DT[w.meta_dtype], zp_mode=zp_mode, norm_scope=norm_scope,
+                                 rotate=0 if rotation_off else 1, scale_mode=o_scale),
                     w.batch, w.n_kv_heads, (cap_pages + 1) * w.page_size)
     return g, o
 
@@ -368,6 +374,40 @@ def test_norm_over_all_kv_heads_bitexact_and_decode(io, meta, bits, kg, n_kv, zp
     if n_kv > 1:
         d0, d1 = ob.debug_dump(g, 1, 0), ob.debug_dump(g, 1, n_kv - 1)
         assert np.array_equal(d0["k_norm"], d1["k_norm"]) and np.array_equal(d0["res_norm"], d1["res_norm"])
+    out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
+@pytest.mark.parametrize("rotation_off,scale,io,meta,bits,path", [
+    (True, "none", "bf16", "f16", 2, "auto"),        # plain per-channel keys / per-token values
+    (True, "l2", "bf16", "f16", 2, "auto"),          # scaling alone (matrix-core kernel)
+    (True, "l2", "bf16", "f16", 2, "generic"),
+    (False, "none", "f16", "f16", 2, "auto"),        # rotation alone
+    (False, "max", "bf16", "f16", 4, "auto"),        # (matrix-core kernel)
+    (False, "mean_abs", "bf16", "f16", 2, "auto"),
+    (True, "mean_abs", "f32", "f32", 2, "auto"),
+])
+def test_ablation_switches_bitexact_and_decode(rotation_off, scale, io, meta, bits, path, monkeypatch):
+    """App. "Ablation Study": rotation off (K and Q un-rotated), scaling off, and the maximum /
+    mean-absolute-value coefficients.  Encoder bit-exact against the oracle with the same
+    switches (prefill + token-by-token appends over a flush), decode in tolerance (the
+    matrix-core kernel takes the cases whose keys are scaled into [-1, 1], the generic one the
+    others)."""
+    ob = _ob()
+    if path == "generic":
+        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 2 + 77,
+                                  io_dtype=io, meta_dtype=meta, bits=bits)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8, rotation_off=rotation_off, scale=scale)
+    n0 = 128 + 101
+    ob.quantize_append(g, to_dev(k[:, :n0], io), to_dev(v[:, :n0], io), eager=True, max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    for t in range(n0, w.context):
+        ob.quantize_append(g, to_dev(k[:, t:t + 1], io), to_dev(v[:, t:t + 1], io))
+        o.append(k[:, t:t + 1], v[:, t:t + 1])
+    assert_cache_equal(g, o, w)
     out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=w.context)
     assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
 

@@ -232,6 +232,20 @@ enum { OSCAR_ROTATE_NORMALIZE = 1u, OSCAR_ROTATE_FAST_RSQRT = 2u };
 int oscar_rotate(const void *x, void *out, void *norms, int64_t n_vec, int32_t io_dtype,
                  int32_t meta_dtype, uint32_t flags, void *stream);
 
+/* Rotation along the row axis of a matrix, for the offline weight preprocessing of Algorithm
+ * "The OScaR algorithm" (OScaR-Preprocess: W_V <- W_V H, W_O <- H W_O, one H per head):
+ *   w   : device [n_rows][n_cols] of io_dtype, row-major, n_rows a multiple of 128
+ *   out : device [n_rows][n_cols] fp32; for every block of 128 rows (one head) and every
+ *         column c: out[128 h + i][c] = sum_j H[i][j] w[128 h + j][c] / sqrt(128)
+ * With W_O stored [n_q_heads*128][d_model] this call is H W_O; W_V stored
+ * [d_model][n_kv_heads*128] takes oscar_rotate (flags 0) on its rows' head segments (H is
+ * symmetric: a row times H is H times the row); the transposed storage convention swaps the
+ * two calls.  The same butterfly order as everywhere else, so results are bit-identical to
+ * oscar_rotate on the transposed matrix.
+ * Returns OSCAR_ERR_INVALID_ARG for NULL pointers, negative sizes or n_rows % 128 != 0. */
+int oscar_rotate_columns(const void *w, void *out, int64_t n_rows, int64_t n_cols,
+                         int32_t io_dtype, void *stream);
+
 /* Measurement aid (not part of the method): a timer owns a pair of HIP events.
  * oscar_decode_attn_partial_timed is oscar_decode_attn_partial with the events attached to
  * the kernel's own dispatch (start/stop events of an extended launch), so that

@@ -29,7 +29,7 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
-           "oscar_probe_stream_read", "oscar_rotate")
+           "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns")
 
 
 class OscarError(RuntimeError):
@@ -98,6 +98,8 @@ def lib():
     L.oscar_timer_elapsed_us.argtypes = [vp, C.POINTER(C.c_float)]
     L.oscar_rotate.restype = C.c_int
     L.oscar_rotate.argtypes = [vp, vp, vp, C.c_int64, i32, i32, C.c_uint32, vp]
+    L.oscar_rotate_columns.restype = C.c_int
+    L.oscar_rotate_columns.argtypes = [vp, vp, C.c_int64, C.c_int64, i32, vp]
     L.oscar_probe_stream_read.restype = C.c_int
     L.oscar_probe_stream_read.argtypes = [vp, sz, i32, vp, vp, vp]
     L.oscar_decode_attn_reduce.restype = C.c_int
@@ -295,6 +297,18 @@ def rotate(x, normalize: bool = False, fast_rsqrt: bool = False, meta_dtype: int
                             n_vec, dtype_code(x.dtype), meta_dtype, flags, _stream_ptr(stream))
     _check(rc, "oscar_rotate")
     return (out, norms) if normalize else out
+
+
+def rotate_columns(w, stream=None):
+    """oscar_rotate_columns on a [n_heads*128, n_cols] matrix: H applied along the rows of every
+    128-row block, fp32 result (OScaR-Preprocess: H W_O)."""
+    import torch
+    assert w.is_cuda and w.is_contiguous() and w.dim() == 2 and w.shape[0] % 128 == 0
+    out = torch.empty(w.shape, dtype=torch.float32, device=w.device)
+    rc = lib().oscar_rotate_columns(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1],
+                                    dtype_code(w.dtype), _stream_ptr(stream))
+    _check(rc, "oscar_rotate_columns")
+    return out
 
 
 def probe_stream_read(src, nbytes: int, workgroups: int, timer: "Timer | None" = None, stream=None):

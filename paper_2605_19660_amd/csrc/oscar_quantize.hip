@@ -73,7 +73,63 @@ int launch_rotate(const void* x, void* out, void* norms, long long n_vec, int me
   return OSCAR_OK;
 }
 
+// H along the row axis: thread = (block of 128 rows, column); the 128 values of a column
+// sit in registers, all seven butterfly stages are register-to-register, and the lanes of a
+// wave read and write consecutive columns.
+template <typename IO>
+__global__ __launch_bounds__(256) void oscar_rotate_columns_kernel(const IO* __restrict__ w,
+                                                                   float* __restrict__ out,
+                                                                   long long n_cols) {
+  const long long c = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_cols) return;
+  const size_t base = (size_t)blockIdx.y * D * (size_t)n_cols + (size_t)c;
+  float x[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) x[j] = to_f32<IO>(w[base + (size_t)j * n_cols]);
+#pragma unroll
+  for (int h = 1; h < D; h <<= 1) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      if ((i & h) == 0) {
+        const float a = x[i], b = x[i | h];
+        x[i] = a + b;
+        x[i | h] = a - b;
+      }
+    }
+  }
+  const float cs = 0.08838834764831845f;  // fp32(1/sqrt(128))
+#pragma unroll
+  for (int j = 0; j < D; ++j) out[base + (size_t)j * n_cols] = x[j] * cs;
+}
+
 }  // namespace
+
+extern "C" int oscar_rotate_columns(const void* w, void* out, int64_t n_rows, int64_t n_cols,
+                                    int32_t io_dtype, void* stream) {
+  if (!w || !out || n_rows < 0 || n_cols < 0 || n_rows % D != 0) return OSCAR_ERR_INVALID_ARG;
+  if (n_rows / D > 65535 || n_cols > ((int64_t)1 << 38)) return OSCAR_ERR_INVALID_ARG;
+  if (n_rows == 0 || n_cols == 0) return OSCAR_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid((unsigned)((n_cols + 255) / 256), (unsigned)(n_rows / D));
+  float* o = reinterpret_cast<float*>(out);
+  switch (io_dtype) {
+    case OSCAR_F32:
+      hipLaunchKernelGGL((oscar_rotate_columns_kernel<float>), grid, dim3(256), 0, st,
+                         reinterpret_cast<const float*>(w), o, (long long)n_cols);
+      break;
+    case OSCAR_BF16:
+      hipLaunchKernelGGL((oscar_rotate_columns_kernel<__hip_bfloat16>), grid, dim3(256), 0, st,
+                         reinterpret_cast<const __hip_bfloat16*>(w), o, (long long)n_cols);
+      break;
+    case OSCAR_F16:
+      hipLaunchKernelGGL((oscar_rotate_columns_kernel<__half>), grid, dim3(256), 0, st,
+                         reinterpret_cast<const __half*>(w), o, (long long)n_cols);
+      break;
+    default: return OSCAR_ERR_INVALID_ARG;
+  }
+  if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+  return OSCAR_OK;
+}
 
 extern "C" int oscar_rotate(const void* x, void* out, void* norms, int64_t n_vec, int32_t io_dtype,
                             int32_t meta_dtype, uint32_t flags, void* stream) {

@@ -87,6 +87,7 @@ def test_split_heuristic_and_host_side_argument_checks_of_the_aids():
     assert ob.decode_auto_splits(ob.Config(32, 8), 1, 0) == 1
     assert L.oscar_rotate(None, None, None, 4, ob.BF16, ob.F16, 0, None) == ob.ERR_INVALID_ARG
     assert L.oscar_probe_stream_read(None, 1 << 20, 4, None, None, None) == ob.ERR_INVALID_ARG
+    assert L.oscar_rotate_columns(None, None, 128, 4, ob.F32, None) == ob.ERR_INVALID_ARG
     assert L.oscar_timer_elapsed_us(None, None) == ob.ERR_INVALID_ARG
     assert L.oscar_timer_destroy(None) == ob.OK
     assert L.oscar_bf16_decode_attn(None, None, None, None, None, ob.BF16, ob.F32, 1, 128, 0, 8, 2, 128,

@@ -3,6 +3,7 @@ not change results and must reject what they cannot run."""
 import numpy as np
 import pytest
 
+import oracle
 from paper_2605_19660_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -95,3 +96,42 @@ def test_stand_alone_rotation_matches_oracle_transforms(io):
     assert np.all(np.abs(n2 - n_ref) <= 2.0 ** -10 * n_ref)
     with pytest.raises(ob.OscarError):
         ob.rotate(xd, normalize=False, fast_rsqrt=True)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_weight_preprocessing_rotations(dt):
+    """OScaR-Preprocess (Algorithm "The OScaR algorithm"): W_V <- W_V H and W_O <- H W_O, one H per
+    head.  W_V H is oscar_rotate on the head segments of W_V's rows, H W_O is
+    oscar_rotate_columns; both bit-exact against the oracle's butterfly, equal to the closed-form
+    Hadamard product, and (X W_V H)(H W_O) = X W_V W_O (H is orthogonal and symmetric)."""
+    import torch
+    ob = _ob()
+    rng = np.random.default_rng(3)
+    d_model, n_kv, n_q = 192, 2, 4          # n_cols not a multiple of the 256-thread block
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dt]
+    w_v = torch.from_numpy(rng.standard_normal((d_model, n_kv * 128)).astype(np.float32)).to(tdt)
+    w_o = torch.from_numpy(rng.standard_normal((n_q * 128, d_model + 77)).astype(np.float32)).to(tdt)
+    wv32, wo32 = w_v.float().numpy(), w_o.float().numpy()
+    got_v = ob.rotate(w_v.cuda().reshape(d_model, n_kv, 128)).cpu().numpy().reshape(d_model, n_kv * 128)
+    got_o = ob.rotate_columns(w_o.cuda()).cpu().numpy()
+    want_v = oracle.fwht(wv32.reshape(d_model, n_kv, 128)).reshape(d_model, n_kv * 128)
+    want_o = oracle.fwht(np.ascontiguousarray(wo32.T).reshape(-1, n_q, 128)).reshape(-1, n_q * 128).T
+    assert np.array_equal(got_v, want_v)
+    assert np.array_equal(got_o, want_o)
+    i = np.arange(128)
+    H = ((-1.0) ** np.array([[bin(a & b).count("1") for b in i] for a in i])) / np.sqrt(128)
+    for h in range(n_q):
+        blk = slice(128 * h, 128 * (h + 1))
+        assert np.allclose(got_o[blk], H @ wo32[blk].astype(np.float64), rtol=1e-5, atol=1e-5)
+    # the rotation cancels between the value projection and the output projection
+    x = rng.standard_normal((5, d_model))
+    g = n_q // n_kv
+    v_plain = (x @ wv32.astype(np.float64)).reshape(5, n_kv, 128)
+    v_rot = (x @ got_v.astype(np.float64)).reshape(5, n_kv, 128)
+    mix = rng.random((n_q, 5, 5))
+    mix /= mix.sum(-1, keepdims=True)        # stand-in for attention probabilities
+    a_plain = np.concatenate([mix[h] @ v_plain[:, h // g] for h in range(n_q)], axis=1)
+    a_rot = np.concatenate([mix[h] @ v_rot[:, h // g] for h in range(n_q)], axis=1)
+    o_plain = a_plain @ wo32.astype(np.float64)
+    o_rot = a_rot @ got_o.astype(np.float64)
+    assert np.abs(o_rot - o_plain).max() <= 1e-4 * np.abs(o_plain).max()

@@ -437,28 +437,46 @@ def test_bf16_comparator_matches_plain_attention_oracle(io):
 
 # ------------------------------------------------- full size, sampled check --
 
-def test_full_size_config1_sampled_against_oracle():
-    """Llama-3-8B-like decode at its full size in the launch configuration the benchmark
-    times: every encoder output of sampled (sequence, kv head) streams bit-exact, decode
+@pytest.mark.parametrize("wi,bits,samples", [
+    (1, 2, ((0, 0), (3, 5), (7, 7))),        # Llama-3-8B-like, batch 8, 32K: the benchmark's workload
+    (2, 2, ((0, 2), (0, 7))),                # batch 1, 128K
+    (3, 4, ((0, 1), (41, 6), (63, 3))),      # batch 64, 8K, INT4
+    (4, 2, ((1, 0), (3, 3))),                # omni-like, GQA 7, 64K
+])
+def test_full_size_configs_sampled_against_oracle(wi, bits, samples):
+    """The benchmark's configurations at their full sizes, in the launch configuration the
+    benchmark times (prefill of the whole context, then a few one-token decode appends, automatic
+    split count): every encoder output of sampled (sequence, kv head) streams bit-exact, decode
     outputs of their query heads within tolerance."""
     torch = _torch()
     ob = _ob()
-    w = synth.LLAMA8B_32K
+    w = synth.CONFIGS[wi].replace(bits=bits)
     kd, vd = synth.make_kv_device(w)
     qh = synth.make_q(w)
-    pages = w.context // w.page_size + 1
-    g, _ = make_pair(w.replace(batch=w.batch), pages)
+    n_extra = 37
+    pages = (w.context + n_extra) // w.page_size + 2
+    g, _ = make_pair(w, pages)
     ob.quantize_append(g, kd, vd, eager=True, max_seq_len_hint=0)
-    out = ob.decode_attn(g, to_dev(qh, w.io_dtype), max_seq_len_hint=w.context).cpu().numpy()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234 + wi)
+    dt = ob.torch_dtype(DT[w.io_dtype])
+    ek = torch.randn(w.batch, n_extra, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    ev = torch.randn(w.batch, n_extra, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    for t in range(n_extra):
+        ob.quantize_append(g, ek[:, t:t + 1].contiguous(), ev[:, t:t + 1].contiguous())
+    out = ob.decode_attn(g, to_dev(qh, w.io_dtype), max_seq_len_hint=w.context + n_extra).cpu().numpy()
     gq = w.n_q_heads // w.n_kv_heads
-    for (b, h) in ((0, 0), (3, 5), (7, 7)):
-        ks = kd[b, :, h].float().cpu().numpy()[None, :, None, :]
-        vs = vd[b, :, h].float().cpu().numpy()[None, :, None, :]
+    for (b, h) in samples:
+        ks = torch.cat([kd[b, :, h], ek[b, :, h]]).float().cpu().numpy()[None, :, None, :]
+        vs = torch.cat([vd[b, :, h], ev[b, :, h]]).float().cpu().numpy()[None, :, None, :]
         o = OracleCache(OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
                                      DT[w.meta_dtype]), 1, 1, pages * w.page_size)
-        o.append(ks, vs, eager=True)
+        o.append(ks[:, :w.context], vs[:, :w.context], eager=True)
+        for t in range(w.context, w.context + n_extra):
+            o.append(ks[:, t:t + 1], vs[:, t:t + 1])
         d = ob.debug_dump(g, b, h)
-        npk = int(o.n_packed[0])
+        npk, nr = int(o.n_packed[0]), int(o.n_res[0])
+        assert (int(d["lens"][0]), int(d["lens"][1])) == (npk + nr, nr)
         assert np.array_equal(d["k_codes"][:npk], o.k_codes[0, 0, :npk])
         assert np.array_equal(d["v_codes"][:npk], o.v_codes[0, 0, :npk])
         assert np.array_equal(d["k_delta"][:npk // w.k_group], o.k_delta[0, 0, :npk // w.k_group])
@@ -466,5 +484,9 @@ def test_full_size_config1_sampled_against_oracle():
         assert np.array_equal(d["k_norm"][:npk], o.k_norm[0, 0, :npk])
         assert np.array_equal(d["v_delta"][:npk], o.v_delta[0, 0, :npk])
         assert np.array_equal(d["v_zero"][:npk], o.v_zero[0, 0, :npk])
+        assert np.array_equal(d["res_k"][:nr], o.res_k[0, 0, :nr])
+        assert np.array_equal(d["res_norm"][:nr], o.res_norm[0, 0, :nr])
         want = o.decode_attn(qh[b:b + 1, h * gq:(h + 1) * gq], nthreads=4)
         assert_decode_close(out[b, h * gq:(h + 1) * gq], want[0])
+    del g, kd, vd
+    torch.cuda.empty_cache()

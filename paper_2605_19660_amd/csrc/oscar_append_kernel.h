@@ -811,9 +811,10 @@ __global__ __launch_bounds__(256) void oscar_token_norm_kernel(AppendParams P) {
   for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
   const SeqPlan sp = plan_sequence(P, b);
   if (sp.n <= 0 || !sp.ok) return;
-  const int ti = blockIdx.x * 16 + (tid >> 4);      // new token of this row
+  const int t_first = (int)blockIdx.x * 16;         // (signed: n_paged below can be negative)
+  const int ti = t_first + (tid >> 4);              // new token of this row
   const int n_paged = sp.nq * R - sp.r0;            // new tokens that go into pages
-  if (blockIdx.x * 16 >= n_paged) return;           // whole workgroup idle
+  if (t_first >= n_paged) return;                   // whole workgroup idle
   const int tc = ti < n_paged ? ti : n_paged - 1;   // whole rows stay active for the exchanges
   const IO* knew = reinterpret_cast<const IO*>(P.k);
   const float nf = token_norm_all_heads<IO, META>(

@@ -152,6 +152,43 @@ def test_incremental_appends_deferred_flush_and_ragged_new_lens():
     assert int(g.dev_status.item()) == 0
 
 
+@pytest.mark.parametrize("seed,bits,kg,vg,norm_all", [(0, 2, 128, 32, False), (1, 4, 32, 64, False),
+                                                       (2, 2, 64, 128, True)])
+def test_random_append_schedules(seed, bits, kg, vg, norm_all):
+    """Seeded random schedules: chunk sizes from 1 to a few blocks, per-sequence lengths
+    (zeros included), prefill and decode rules mixed.  After every call the whole cache state is
+    bit-exact against the oracle; the decode is checked every few calls."""
+    torch = _torch()
+    ob = _ob()
+    rng = np.random.default_rng(1000 + seed)
+    w = synth.LLAMA8B_32K.replace(batch=3, n_q_heads=6, n_kv_heads=3, context=1500, bits=bits,
+                                  k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 14, norm_scope=1 if norm_all else 0)
+    pos = np.zeros(w.batch, np.int64)
+    for call in range(24):
+        T = int(rng.choice([1, 1, 2, 17, 127, 128, 129, 200, 300]))
+        lens = [int(rng.integers(0, T + 1)) if rng.random() < 0.5 else T for _ in range(w.batch)]
+        lens = [min(n, w.context - int(pos[b])) for b, n in enumerate(lens)]
+        eager = bool(rng.random() < 0.4)
+        kk = np.zeros((w.batch, T, w.n_kv_heads, w.head_dim), np.float32)
+        vv = np.zeros_like(kk)
+        for b in range(w.batch):
+            kk[b, :lens[b]] = k[b, pos[b]:pos[b] + lens[b]]
+            vv[b, :lens[b]] = v[b, pos[b]:pos[b] + lens[b]]
+        nl = np.asarray(lens, np.int32)
+        ob.quantize_append(g, to_dev(kk, w.io_dtype), to_dev(vv, w.io_dtype),
+                           new_lens=torch.from_numpy(nl).cuda(), eager=eager)
+        o.append(kk, vv, new_lens=nl, eager=eager)
+        pos += nl
+        assert_cache_equal(g, o, w)
+        if call % 4 == 3:
+            q = synth.make_q(w, call)
+            out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=max(1, int(pos.max())))
+            assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+    assert int(g.dev_status.item()) == 0
+
+
 def test_token_by_token_equals_bulk_on_gpu():
     ob = _ob()
     w = synth.LLAMA8B_32K.replace(batch=1, n_q_heads=4, n_kv_heads=1, context=300)

@@ -237,6 +237,49 @@ def test_decode_gqa_variants_split_and_page_permutation_invariance(hq, hkv, bits
     assert torch.equal(ob16.float().cpu(), torch.from_numpy(outs[2]).to(torch.bfloat16).float())
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_decode_configurations(seed):
+    """Seeded random draws over the decode's whole argument space: GQA group, bits, group sizes
+    (both kernels), element types, zero-point form, ablation switches, batch, ragged lengths
+    (empty, residual-only and exact-page sequences included), a permuted block table and the
+    split count.  Encoder bit-exact, decode within tolerance, every time."""
+    torch = _torch()
+    ob = _ob()
+    rng = np.random.default_rng(7000 + seed)
+    hkv = int(rng.choice([1, 2, 3]))
+    gq = int(rng.choice([1, 2, 4, 5, 7, 8]))
+    bits = int(rng.choice([2, 4]))
+    kg, vg = [(128, 32), (32, 32), (128, 128), (64, 64), (32, 128)][int(rng.integers(5))]
+    io, meta = [("bf16", "f16"), ("f16", "f16"), ("bf16", "f32"), ("f32", "f16")][int(rng.integers(4))]
+    zp = int(rng.integers(2))
+    rotation_off = bool(rng.random() < 0.25)
+    scale = str(rng.choice(["l2", "l2", "l2", "max", "mean_abs", "none"]))
+    norm_all = bool(scale == "l2" and rng.random() < 0.3)
+    batch = int(rng.integers(1, 5))
+    eager = bool(rng.random() < 0.7)
+    splits = int(rng.choice([0, 1, 2, 3, 7, 16]))
+    cap = 10
+    w = synth.LLAMA8B_32K.replace(batch=batch, n_q_heads=hkv * gq, n_kv_heads=hkv, context=cap * 128 - 1,
+                                  io_dtype=io, meta_dtype=meta, bits=bits, k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w, seed)
+    perm = rng.permutation(batch * cap)
+    g, o = make_pair(w, cap, page_perm=perm, zp_mode=zp, norm_scope=1 if norm_all else 0,
+                     rotation_off=rotation_off, scale=scale)
+    special = [0, 57, 128, 256, 1, 127, 129]
+    lens = np.array([int(rng.choice(special)) if rng.random() < 0.4 else int(rng.integers(0, w.context + 1))
+                     for _ in range(batch)], np.int32)
+    T = max(1, int(lens.max()))
+    ob.quantize_append(g, to_dev(k[:, :T], io), to_dev(v[:, :T], io), eager=eager,
+                       new_lens=torch.from_numpy(lens).cuda(), max_seq_len_hint=0)
+    o.append(k[:, :T], v[:, :T], new_lens=lens, eager=eager)
+    assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, io), max_seq_len_hint=T, num_splits=splits).cpu().numpy()
+    assert np.isfinite(out).all()
+    assert_decode_close(out, o.decode_attn(q))
+    assert int(g.dev_status.item()) == 0
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 def test_decode_long_stream_one_split_crosses_block_table_chunks(bits):
     """One split over 300 pages: every wave walks 75 pages, more than the 64 block-table entries

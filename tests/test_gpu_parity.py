@@ -515,6 +515,37 @@ def test_bf16_comparator_matches_plain_attention_oracle(io):
         assert_decode_close(out, want)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_bf16_comparator_random_shapes(seed):
+    """Seeded random GQA groups, lengths (zero and one included), capacities that are no multiple
+    of the kernel's token step, split counts and both layouts."""
+    torch = _torch()
+    ob = _ob()
+    rng = np.random.default_rng(8100 + seed)
+    hkv = int(rng.choice([1, 2, 4]))
+    gq = int(rng.choice([1, 2, 4, 7, 8]))
+    io = str(rng.choice(["bf16", "f16"]))
+    batch = int(rng.integers(1, 5))
+    S = int(rng.choice([1, 3, 64, 257, 1000, 1531]))
+    w = synth.LLAMA8B_32K.replace(batch=batch, n_q_heads=hkv * gq, n_kv_heads=hkv, context=S, io_dtype=io)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w, seed)
+    lens = np.array([int(rng.choice([0, 1, S])) if rng.random() < 0.4 else int(rng.integers(0, S + 1))
+                     for _ in range(batch)], np.int32)
+    want = oracle.plain_attn(q, k, v, seq_lens=lens)
+    splits = int(rng.choice([1, 2, 5, 16]))
+    kd, vd = to_dev(k, io), to_dev(v, io)
+    if rng.random() < 0.5:
+        out = ob.bf16_decode_attn(to_dev(q, io), kd, vd, torch.from_numpy(lens).cuda(), num_splits=splits)
+    else:
+        out = ob.bf16_decode_attn(to_dev(q, io), kd.permute(0, 2, 1, 3).contiguous(),
+                                  vd.permute(0, 2, 1, 3).contiguous(), torch.from_numpy(lens).cuda(),
+                                  num_splits=splits, head_major=True)
+    out = out.cpu().numpy()
+    assert np.isfinite(out).all()
+    assert_decode_close(out, want)
+
+
 # ------------------------------------------------- full size, sampled check --
 
 @pytest.mark.parametrize("wi,bits,samples", [

@@ -97,11 +97,14 @@ extern "C" int32_t oscar_decode_auto_splits(const oscar_config* cfg, int32_t bat
     n_cu = prop.multiProcessorCount;
   const int pages = max_seq_len > 0 ? (max_seq_len + OSCAR_R - 1) / OSCAR_R : 1;
   const int units = batch * cfg->n_kv_heads;
-  // two workgroups (8 waves) per CU are resident at a time (one when more than 4 query heads
-  // share a kv head: that kernel variant needs the whole register file) and every wave wants
-  // at least two pages: aim at one round of workgroups
+  // two workgroups (8 waves) per CU are resident at a time (one for the register-hungry
+  // variants, see oscar_decode_mfma_wgs_per_cu) and every wave wants at least two pages: aim
+  // at one round of workgroups
   const int gq = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 1;
-  int splits = ((gq > 4 ? 1 : 2) * n_cu) / units;
+  const int ngk = cfg->k_group > 0 ? OSCAR_R / cfg->k_group : 1;
+  const int ngv = cfg->v_group > 0 ? OSCAR_D / cfg->v_group : 1;
+  const int resident = oscar_decode_mfma_wgs_per_cu(cfg->bits, gq > 4 ? 2 : 1, ngk, ngv);
+  int splits = (resident * n_cu) / units;
   const int max_by_pages = pages / 8 > 0 ? pages / 8 : 1;
   if (splits > max_by_pages) splits = max_by_pages;
   if (splits < 1) splits = 1;

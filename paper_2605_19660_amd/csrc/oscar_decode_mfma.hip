@@ -369,11 +369,18 @@ __device__ __forceinline__ float max8_halves(const uint4& r) {
 // accumulator lane group q4 (rows 4*q4..4*q4+3) owns heads q4 (slot 0) and q4+4 (slot 1).
 __device__ __forceinline__ int row_hi(int h) { return 4 * (h & 3) + 2 * (h >> 2); }
 
-// HP = head slots per accumulator lane group: 1 for up to 4 query heads per kv head (two
-// workgroups per CU), 2 for 5..8 (twice the per-head registers: one workgroup per CU, the
-// overflow lives in accumulation registers instead of scratch memory).
+// HP = head slots per accumulator lane group: 1 for up to 4 query heads per kv head, 2 for
+// 5..8 (twice the per-head registers).  Two workgroups per CU wherever the registers allow it
+// without scratch memory: every one-slot variant, and the two-slot variants with one key group
+// per page and 2-bit codes or one value group; the remaining two-slot variants run one
+// workgroup per CU (their overflow then lives in accumulation registers).
+__host__ __device__ constexpr int decode_mfma_wgs_per_cu(int bits, int hp, int ngk, int ngv) {
+  return oscar_decode_mfma_wgs_per_cu(bits, hp, ngk, ngv);
+}
+
 template <int BITS, int HP, int NGK, int NGV>
-__global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
+__global__ __launch_bounds__(256, decode_mfma_wgs_per_cu(BITS, HP, NGK, NGV))
+void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   constexpr int TPG = 8 / NGK;  // token tiles per key group
   constexpr int CPG = 8 / NGV;  // channel tiles per value group
   constexpr int TABW = D + 8;   // operand table row stride in halves
@@ -383,6 +390,9 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
   __shared__ __align__(16) _Float16 s_P[4][16][TABW];   // per wave: (p Delta_v) hi/lo rows
   __shared__ __align__(16) float s_o[4][OSCAR_MAX_GQA][D];  // wave results for the merge
   __shared__ float s_wm[4][OSCAR_MAX_GQA], s_wl[4][OSCAR_MAX_GQA];
+  // two head slots: the rotated queries in operand order wait in LDS between pages instead of
+  // registers (16 registers that the second slot's softmax state needs)
+  __shared__ __align__(16) float4 s_qr[HP == 2 ? 4 : 1][HP == 2 ? 2 : 1][2][HP == 2 ? 64 : 1];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -582,6 +592,10 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
 #pragma unroll
     for (int i = 0; i < 8; ++i) qs[s][i] = ldexpf(qr[s][i], xh - slot_bitpos(BITS, n & 3, i));
     ps[s] = ldexpf(1.0f, 24 - xh);
+    if constexpr (HP == 2) {
+      s_qr[wave][s][0][lane] = make_float4(qr[s][0], qr[s][1], qr[s][2], qr[s][3]);
+      s_qr[wave][s][1][lane] = make_float4(qr[s][4], qr[s][5], qr[s][6], qr[s][7]);
+    }
   }
   // value side: this lane's tokens 16*T+n feed k-step n/4, element T
   float vsc0[8];
@@ -627,8 +641,15 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
 #pragma unroll
         for (int s = 0; s < HP; ++s) {
           float bp = 0.0f;
+          if constexpr (HP == 2) {
+            const float4 qa = s_qr[wave][s][0][lane], qb = s_qr[wave][s][1][lane];
+            const float qv[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
 #pragma unroll
-          for (int i = 0; i < 8; ++i) bp = fmaf(qr[s][i], dz[i], bp);
+            for (int i = 0; i < 8; ++i) bp = fmaf(qv[i], dz[i], bp);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bp = fmaf(qr[s][i], dz[i], bp);
+          }
           bias[s] = row16_sum(bp);
           uint4 hi, lo;
           mul_split_hi_lo(qs[s], kr.kd[g], hi, lo);
@@ -649,17 +670,35 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
         for (int tt = 0; tt < TPG; tt += 2) {
           // two token tiles at a time: independent accumulators keep the MFMA pipe busy
           const int T = g * TPG + tt;
-          u32x4 b0[4], b1[4];
-          kr.kc[T >> 1].chunk(0).operands(b0, masks);
-          kr.kc[T >> 1].chunk(1).operands(b1, masks);
-          kr.load_codes(nx, T >> 1, lane);
           float4v acc0 = (float4v){0.0f, 0.0f, 0.0f, 0.0f}, acc1 = acc0;
+          if constexpr (HP == 1) {
+            u32x4 b0[4], b1[4];
+            kr.kc[T >> 1].chunk(0).operands(b0, masks);
+            kr.kc[T >> 1].chunk(1).operands(b1, masks);
+            kr.load_codes(nx, T >> 1, lane);
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                areg[kk], __builtin_bit_cast(half8, b0[kk]), acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-                areg[kk], __builtin_bit_cast(half8, b1[kk]), acc1, 0, 0, 0);
+            for (int kk = 0; kk < 4; ++kk) {
+              acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  areg[kk], __builtin_bit_cast(half8, b0[kk]), acc0, 0, 0, 0);
+              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  areg[kk], __builtin_bit_cast(half8, b1[kk]), acc1, 0, 0, 0);
+            }
+          } else {
+            // one tile at a time: the second head slot needs the registers of the second
+            // operand set (the other wave of the SIMD fills the matrix pipe instead)
+            u32x4 b0[4];
+            kr.kc[T >> 1].chunk(0).operands(b0, masks);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+              acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  areg[kk], __builtin_bit_cast(half8, b0[kk]), acc0, 0, 0, 0);
+            asm volatile("" ::: "memory");
+            kr.kc[T >> 1].chunk(1).operands(b0, masks);
+            kr.load_codes(nx, T >> 1, lane);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+              acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                  areg[kk], __builtin_bit_cast(half8, b0[kk]), acc1, 0, 0, 0);
           }
 #pragma unroll
           for (int s = 0; s < HP; ++s) {
@@ -760,16 +799,32 @@ __global__ __launch_bounds__(256, HP == 1 ? 2 : 1) void oscar_decode_mfma_kernel
 #pragma unroll
       for (int cc = 0; cc < CPG; cc += 2) {
         const int ct = g * CPG + cc;
-        u32x4 b0[4], b1[4];
-        vr.vc[ct >> 1].chunk(0).operands(b0, masks);
-        vr.vc[ct >> 1].chunk(1).operands(b1, masks);
-        vr.load_codes(nx, ct >> 1, lane);
+        if constexpr (HP == 1) {
+          u32x4 b0[4], b1[4];
+          vr.vc[ct >> 1].chunk(0).operands(b0, masks);
+          vr.vc[ct >> 1].chunk(1).operands(b1, masks);
+          vr.load_codes(nx, ct >> 1, lane);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-              preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct], 0, 0, 0);
-          O[ct + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
-              preg[kk], __builtin_bit_cast(half8, b1[kk]), O[ct + 1], 0, 0, 0);
+          for (int kk = 0; kk < 4; ++kk) {
+            O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct], 0, 0, 0);
+            O[ct + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                preg[kk], __builtin_bit_cast(half8, b1[kk]), O[ct + 1], 0, 0, 0);
+          }
+        } else {
+          u32x4 b0[4];
+          vr.vc[ct >> 1].chunk(0).operands(b0, masks);
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct], 0, 0, 0);
+          asm volatile("" ::: "memory");
+          vr.vc[ct >> 1].chunk(1).operands(b0, masks);
+          vr.load_codes(nx, ct >> 1, lane);
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            O[ct + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct + 1], 0, 0, 0);
         }
       }
     }

@@ -77,11 +77,12 @@ def test_null_arguments_are_rejected_before_any_launch():
 
 def test_split_heuristic_and_host_side_argument_checks_of_the_aids():
     """Host logic that needs no GPU: the split count aims at one round of resident workgroups
-    (two per CU, one for more than 4 query heads per kv head; 256 CUs assumed without a device)
+    (two per CU, one for the register-hungry two-slot variants; 256 CUs assumed without a device)
     and never gives a wave fewer than two pages; the aids reject bad arguments before any launch."""
     L = ob.lib()
     assert ob.decode_auto_splits(ob.Config(32, 8), 8, 32768) == 8            # 512 / 64 units
-    assert ob.decode_auto_splits(ob.Config(28, 4), 4, 65536) == 16           # 256 / 16 units (g = 7)
+    assert ob.decode_auto_splits(ob.Config(28, 4), 4, 65536) == 32           # 512 / 16 units (g = 7)
+    assert ob.decode_auto_splits(ob.Config(28, 4, bits=4), 4, 65536) == 16   # that variant: one per CU
     assert ob.decode_auto_splits(ob.Config(32, 8), 1, 4096) == 4             # 32 pages / 8
     assert ob.decode_auto_splits(ob.Config(32, 8), 64, 8192) == 1
     assert ob.decode_auto_splits(ob.Config(32, 8), 1, 0) == 1

@@ -161,8 +161,14 @@ def measure(args, w, np, torch, ob, synth):
 
     # ---- prefill: quantize_append of the whole context, timed per copy ----
     caches, t_pre = [], []
-    for _ in range(n_copies):
+    for ci in range(n_copies):
         c = ob.Cache(cfg, w.batch, pages)
+        if ci == 0:
+            # untimed first launch of this kernel instantiation (code load), then start over
+            ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0, stream=stream)
+            torch.cuda.synchronize()
+            c.seq_lens.zero_()
+            c.res_lens.zero_()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0, stream=stream)

@@ -384,6 +384,9 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   constexpr int TPG = 8 / NGK;  // token tiles per key group
   constexpr int CPG = 8 / NGV;  // channel tiles per value group
   constexpr int TABW = D + 8;   // operand table row stride in halves
+  // operand tiles unpacked one at a time (instead of in pairs) where the pair's second
+  // register set would not fit
+  constexpr bool ONE_TILE = (HP == 2) || (NGK == 4);
 
   // rows padded by 16 bytes: the 16-byte operand reads of lanes n = 0..7 hit 8 different banks
   __shared__ __align__(16) _Float16 s_A[4][16][TABW];   // per wave: (Q_h Delta_k) hi/lo rows
@@ -671,7 +674,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
           // two token tiles at a time: independent accumulators keep the MFMA pipe busy
           const int T = g * TPG + tt;
           float4v acc0 = (float4v){0.0f, 0.0f, 0.0f, 0.0f}, acc1 = acc0;
-          if constexpr (HP == 1) {
+          if constexpr (!ONE_TILE) {
             u32x4 b0[4], b1[4];
             kr.kc[T >> 1].chunk(0).operands(b0, masks);
             kr.kc[T >> 1].chunk(1).operands(b1, masks);
@@ -799,7 +802,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 #pragma unroll
       for (int cc = 0; cc < CPG; cc += 2) {
         const int ct = g * CPG + cc;
-        if constexpr (HP == 1) {
+        if constexpr (!ONE_TILE) {
           u32x4 b0[4], b1[4];
           vr.vc[ct >> 1].chunk(0).operands(b0, masks);
           vr.vc[ct >> 1].chunk(1).operands(b1, masks);

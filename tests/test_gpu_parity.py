@@ -280,6 +280,31 @@ def test_random_decode_configurations(seed):
     assert int(g.dev_status.item()) == 0
 
 
+@pytest.mark.parametrize("path", ["mfma", "generic"])
+@pytest.mark.parametrize("scale", [0.03, 0.25])
+def test_decode_custom_softmax_scale(path, scale, monkeypatch):
+    """softmax_scale > 0 replaces 1/sqrt(d) in both decode kernels and in the comparator."""
+    torch = _torch()
+    ob = _ob()
+    if path == "generic":
+        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 4 + 33)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 6)
+    ob.quantize_append(g, to_dev(k, w.io_dtype), to_dev(v, w.io_dtype), eager=True, max_seq_len_hint=0)
+    o.append(k, v, eager=True)
+    out = ob.decode_attn(g, to_dev(q, w.io_dtype), scale=scale, max_seq_len_hint=w.context).cpu().numpy()
+    want = o.decode_attn(q, scale=scale)
+    assert_decode_close(out, want)
+    assert np.abs(want - o.decode_attn(q)).max() > 1e-2      # the scale matters on these inputs
+    if path == "mfma":
+        lens = torch.full((w.batch,), w.context, dtype=torch.int32, device="cuda")
+        outp = ob.bf16_decode_attn(to_dev(q, w.io_dtype), to_dev(k, w.io_dtype), to_dev(v, w.io_dtype),
+                                   lens, scale=scale).cpu().numpy()
+        assert_decode_close(outp, oracle.plain_attn(q, k, v, scale=scale))
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 def test_decode_long_stream_one_split_crosses_block_table_chunks(bits):
     """One split over 300 pages: every wave walks 75 pages, more than the 64 block-table entries

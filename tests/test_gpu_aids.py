@@ -135,3 +135,49 @@ def test_weight_preprocessing_rotations(dt):
     o_plain = a_plain @ wo32.astype(np.float64)
     o_rot = a_rot @ got_o.astype(np.float64)
     assert np.abs(o_rot - o_plain).max() <= 1e-4 * np.abs(o_plain).max()
+
+
+def test_everything_runs_on_the_callers_stream():
+    """Append, decode (both passes, timed and untimed) and rotation enqueued on a side stream
+    (default priority) give the results of the default stream, and nothing runs before the side
+    stream is released: the library only enqueues on the stream it is given."""
+    import torch
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 3 + 40)
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads)
+    k, v = synth.make_kv_batch(w)
+    kd, vd = torch.from_numpy(k).cuda().bfloat16(), torch.from_numpy(v).cuda().bfloat16()
+    q = torch.from_numpy(synth.make_q(w)).cuda().bfloat16()
+    ref = ob.Cache(cfg, w.batch, 6)
+    ob.quantize_append(ref, kd, vd, eager=True, max_seq_len_hint=0)
+    want = ob.decode_attn(ref, q, max_seq_len_hint=w.context, num_splits=3)
+    want_rot = ob.rotate(q)
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    c = ob.Cache(cfg, w.batch, 6)
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, 3), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    gate = torch.cuda.Event()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        # a long-running fill keeps the side stream busy while the calls below are enqueued
+        big = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        for _ in range(8):
+            big.fill_(1)
+        ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0, stream=side)
+        tm = ob.Timer()
+        ob.decode_attn_partial(c, q, ws, 3, stream=side, timer=tm)
+        ob.decode_attn_reduce(c, out, ws, 3, stream=side)
+        rot = ob.rotate(q, stream=side)
+        gate.record(side)
+    gate.synchronize()
+    assert tm.elapsed_us() > 0
+    tm.close()
+    assert torch.equal(out, want)
+    assert torch.equal(rot, want_rot)
+    assert torch.equal(c.seq_lens, ref.seq_lens) and torch.equal(c.res_lens, ref.res_lens)
+    da, db = ob.debug_dump(c, 1, 1), ob.debug_dump(ref, 1, 1)
+    npk = 128 * 3
+    for name in ("k_codes", "v_codes", "k_norm", "v_delta"):
+        assert np.array_equal(da[name][:npk], db[name][:npk]), name

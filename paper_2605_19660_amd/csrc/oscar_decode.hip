@@ -392,9 +392,12 @@ int launch_gq(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipEvent
               hipEvent_t e1) {
   switch (gq) {
 #define OSCAR_CASE(G) \
-  case G:                                                                                  \
-    hipExtLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st, e0, \
-                          e1, 0, P);                                                       \
+  case G:                                                                                     \
+    if (e0 || e1)                                                                             \
+      hipExtLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st,   \
+                            e0, e1, 0, P);                                                    \
+    else                                                                                      \
+      hipLaunchKernelGGL((oscar_decode_partial_kernel<BITS, G>), grid, dim3(256), 0, st, P);  \
     break;
     OSCAR_CASE(1) OSCAR_CASE(2) OSCAR_CASE(3) OSCAR_CASE(4)
     OSCAR_CASE(5) OSCAR_CASE(6) OSCAR_CASE(7) OSCAR_CASE(8)

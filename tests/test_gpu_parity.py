@@ -517,6 +517,63 @@ def test_ablation_switches_bitexact_and_decode(rotation_off, scale, io, meta, bi
     assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
 
 
+# ----------------------------------------------------------------- graphs --
+
+@pytest.mark.parametrize("path", ["mfma", "generic"])
+def test_decode_step_replays_from_a_captured_graph(path, monkeypatch):
+    """Sequence lengths live on the device and every entry point only enqueues, so a whole decode
+    step (append one token, partial pass, reduce) can be captured once and replayed: 40 replays
+    with fresh tokens and queries, eager work and synchronizations in between, each compared
+    bit for bit with the same step run eagerly on a twin cache; the replays cross a residual
+    flush.  At the end the replayed cache is bit-exact against the oracle."""
+    torch = _torch()
+    ob = _ob()
+    if path == "generic":
+        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+    n0, steps, splits = 128 * 2 + 100, 40, 3
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=n0 + steps)
+    k, v = synth.make_kv_batch(w)
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    gc, o = make_pair(w, 5)
+    ec, _ = make_pair(w, 5)
+    warm, _ = make_pair(w, 5)
+    for c in (gc, ec, warm):
+        ob.quantize_append(c, kd[:, :n0].contiguous(), vd[:, :n0].contiguous(), eager=True, max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    sk, sv = torch.zeros_like(kd[:, :1]).contiguous(), torch.zeros_like(vd[:, :1]).contiguous()
+    sq = torch.zeros(w.batch, w.n_q_heads, 128, dtype=kd.dtype, device="cuda")
+    ws = torch.empty(ob.decode_workspace_bytes(gc.cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    ws_e = torch.empty_like(ws)
+    out_g = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    out_e = torch.zeros_like(out_g)
+
+    def step(c, kk, vv, qq, wsp, out):
+        ob.quantize_append(c, kk, vv)
+        ob.decode_attn_partial(c, qq, wsp, splits)
+        ob.decode_attn_reduce(c, out, wsp, splits)
+
+    step(warm, sk, sv, sq, ws, out_g)          # every kernel loaded before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(gc, sk, sv, sq, ws, out_g)
+    # (the capture itself enqueued nothing: the cache is still at n0 tokens)
+    torch.cuda.synchronize()
+    assert int(gc.seq_lens[0].item()) == n0
+    for t in range(steps):
+        q = to_dev(synth.make_q(w, t), w.io_dtype)
+        sk.copy_(kd[:, n0 + t:n0 + t + 1])
+        sv.copy_(vd[:, n0 + t:n0 + t + 1])
+        sq.copy_(q)
+        graph.replay()
+        step(ec, kd[:, n0 + t:n0 + t + 1].contiguous(), vd[:, n0 + t:n0 + t + 1].contiguous(), q, ws_e, out_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), t
+        o.append(k[:, n0 + t:n0 + t + 1], v[:, n0 + t:n0 + t + 1])
+    assert_cache_equal(gc, o, w)
+    assert_decode_close(out_g.cpu().numpy(), o.decode_attn(synth.make_q(w, steps - 1)))
+
+
 # -------------------------------------------------------------- comparator --
 
 @pytest.mark.parametrize("io", ["bf16", "f16"])

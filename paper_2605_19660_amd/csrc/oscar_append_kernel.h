@@ -4,9 +4,9 @@
 // algorithm"; key transform of App. "Implementation Details ...", "Overall Design";
 // quantizer of Eq. 3-4).
 //
-// Every translation unit that includes this header is compiled with -ffp-contract=off: the encoder is an
-// encoding, and its fp32 operation order is part of the format (codes must not
-// depend on whether a multiply-add was fused).
+// Every translation unit that includes this header is compiled with -ffp-contract=off:
+// the encoder is an encoding, and its fp32 operation order is part of the format (codes
+// must not depend on whether a multiply-add was fused).
 //
 // Work decomposition: one workgroup of 256 threads per (sequence, kv head, block of
 // R=128 pending tokens).  A thread owns 8 channels (channel group cg) of token
@@ -30,7 +30,6 @@
 #include "oscar_common.h"
 #include "oscar_rowops.h"
 
-
 struct AppendParams {
   const void* k;
   const void* v;
@@ -41,8 +40,9 @@ struct AppendParams {
   uint32_t flags;
 };
 
-// The encoder instantiations with one norm over all kv heads live in a translation unit of
-// their own (they need more registers; kept apart they cost the default path nothing).
+// The encoder instantiations with one norm over all kv heads (and the norm pre-pass they
+// need) live in a translation unit of their own: the two sets compile side by side and the
+// default path's register allocation does not depend on the variant's code.
 int oscar_launch_append_all_heads(const AppendParams& P, dim3 grid, hipStream_t st);
 
 namespace {

@@ -355,7 +355,8 @@ static void quantize_block(const stream_view *s, int pos) {
  * (sequence, head).  `np`/`nr` are that sequence's packed / residual counts on
  * entry; the new counts are returned through them.
  *   eager = 1 : prefill rule, every completed block of R tokens is quantized,
- *               the tail (< R) stays in the residual.
+ *               the tail (< R) stays in the residual.  The algorithm acts on arriving
+ *               tokens: with n = 0 nothing happens under either rule.
  *   eager = 0 : decode rule, a block completed by this call stays in the
  *               residual (so the attention that follows still sees it in FP16,
  *               as in OScaR-Inference where attention precedes BufferQuant)
@@ -382,7 +383,7 @@ static void stream_append(const stream_view *s, const float *k, const float *v, 
     for (int j = 0; j < d; ++j) s->res_v[(size_t)(*nr) * d + j] = v[(size_t)t * row_stride + j];
     *nr += 1;
   }
-  if (eager && *nr == R) {
+  if (eager && n > 0 && *nr == R) {   /* (a call that brings no token changes nothing) */
     quantize_block(s, *np);
     *np += R;
     *nr = 0;

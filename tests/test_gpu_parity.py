@@ -189,6 +189,40 @@ def test_random_append_schedules(seed, bits, kg, vg, norm_all):
     assert int(g.dev_status.item()) == 0
 
 
+def test_empty_appends_change_nothing_even_on_a_full_residual():
+    """A call that brings a sequence no token leaves it untouched under either rule: a full
+    16-bit residual (completed by a decode-rule append) keeps waiting through prefill-rule calls
+    with new_lens = 0 and through T = 0 calls, and is flushed by the next token."""
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=4, n_kv_heads=2, context=400)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 5)
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    ob.quantize_append(g, kd[:, :128].contiguous(), vd[:, :128].contiguous())     # residual full, not flushed
+    o.append(k[:, :128], v[:, :128])
+    assert_cache_equal(g, o, w)
+    assert int(g.res_lens[0].item()) == 128
+    nl = np.asarray([0, 5], np.int32)                                              # sequence 0 gets nothing
+    ob.quantize_append(g, kd[:, 128:133].contiguous(), vd[:, 128:133].contiguous(), eager=True,
+                       new_lens=torch.from_numpy(nl).cuda())
+    o.append(k[:, 128:133], v[:, 128:133], new_lens=nl, eager=True)
+    assert_cache_equal(g, o, w)
+    assert g.res_lens.tolist() == [128, 5] and g.seq_lens.tolist() == [128, 133]
+    ob.quantize_append(g, kd[:, :0].contiguous(), vd[:, :0].contiguous(), eager=True)   # T = 0
+    o.append(k[:, :0], v[:, :0], eager=True)
+    assert_cache_equal(g, o, w)
+    nl = np.asarray([1, 0], np.int32)
+    ob.quantize_append(g, kd[:, 128:129].contiguous(), vd[:, 128:129].contiguous(),
+                       new_lens=torch.from_numpy(nl).cuda())
+    o.append(k[:, 128:129], v[:, 128:129], new_lens=nl)
+    assert_cache_equal(g, o, w)
+    assert g.res_lens.tolist() == [1, 5] and g.seq_lens.tolist() == [129, 133]
+    q = synth.make_q(w)
+    out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=133)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
 def test_token_by_token_equals_bulk_on_gpu():
     ob = _ob()
     w = synth.LLAMA8B_32K.replace(batch=1, n_q_heads=4, n_kv_heads=1, context=300)

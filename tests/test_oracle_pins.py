@@ -238,7 +238,6 @@ def test_all_heads_norm_in_the_cache():
     for s in (1, 127, 1, 100, 71):
         pos = int(b.n_packed[0] + b.n_res[0])
         b.append(k[:, pos:pos + s], v[:, pos:pos + s])
-    b.append(k[:, :0], v[:, :0], eager=True)
     for name in ("n_packed", "n_res", "k_codes", "k_delta", "k_zero", "k_norm", "v_codes", "v_delta", "v_zero"):
         assert np.array_equal(getattr(a, name), getattr(b, name)), name
     p = OracleCache(OracleConfig(128, 2, 128, 32, 128, F16), k.shape[0], 2, 512)
@@ -393,6 +392,50 @@ def test_bulk_equals_incremental_ingestion():
         assert np.array_equal(getattr(a, name), getattr(b, name)), name
     nr = int(a.n_res[0])
     assert np.array_equal(a.res_k[:, :, :nr], b.res_k[:, :, :nr])
+
+
+def test_any_append_schedule_quantizes_the_same_blocks():
+    """Algorithm "The OScaR algorithm", BufferQuantK / BufferQuantV: a block of R tokens is
+    quantized on its own, so whatever the schedule (chunk sizes, prefill or decode rule, empty
+    calls), the packed region must be a prefix of what one eager bulk call produces, the counts
+    must add up, and the residual must hold exactly the remaining tokens' 16-bit keys."""
+    from hypothesis import given, settings, strategies as st
+    w = synth.TINY.replace(n_kv_heads=2, n_q_heads=2)
+    k, v = synth.make_kv_batch(w, 0, 700)
+    bulk = OracleCache(OracleConfig(128, 2, 64, 32, 128, F16), 1, 2, 1024)
+    bulk.append(k, v, eager=True)
+    # every token's 16-bit normalized key, from a cache that never flushes
+    keep = OracleCache(OracleConfig(128, 2, 64, 32, 128, F16), 1, 2, 1024)
+    ku = np.zeros((2, 700, 128), np.float32)
+    for t0 in range(0, 700, 100):
+        one = OracleCache(OracleConfig(128, 2, 64, 32, 128, F16), 1, 2, 128)
+        one.append(k[:, t0:t0 + 100], v[:, t0:t0 + 100])
+        ku[:, t0:t0 + 100] = one.res_k[0, :, :100]
+    del keep
+
+    @settings(max_examples=40, deadline=None)
+    @given(st.lists(st.tuples(st.integers(0, 300), st.booleans()), min_size=1, max_size=12))
+    def run(schedule):
+        c = OracleCache(OracleConfig(128, 2, 64, 32, 128, F16), 1, 2, 1024)
+        pos = 0
+        for n, eager in schedule:
+            n = min(n, 700 - pos)
+            before = (int(c.n_packed[0]), int(c.n_res[0]))
+            c.append(k[:, pos:pos + n], v[:, pos:pos + n], eager=eager)
+            pos += n
+            npk, nr = int(c.n_packed[0]), int(c.n_res[0])
+            assert npk + nr == pos and npk % 128 == 0 and 0 <= nr <= 128
+            assert nr < 128 or not eager or n == 0      # the prefill rule leaves no full residual
+            if n == 0:
+                assert (npk, nr) == before              # an empty call changes nothing
+        npk, nr = int(c.n_packed[0]), int(c.n_res[0])
+        for name in ("k_codes", "v_codes", "k_norm", "v_delta", "v_zero"):
+            assert np.array_equal(getattr(c, name)[0, :, :npk], getattr(bulk, name)[0, :, :npk]), name
+        assert np.array_equal(c.k_delta[0, :, :npk // 64], bulk.k_delta[0, :, :npk // 64])
+        assert np.array_equal(c.res_k[0, :, :nr], ku[:, npk:npk + nr])
+        assert np.array_equal(c.res_v[0, :, :nr], np.moveaxis(v[0, npk:npk + nr], 1, 0))
+
+    run()
 
 
 # ------------------------------------------------------------------ decode --

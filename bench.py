@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations")
     ap.add_argument("--bits", type=int, default=0, help="override bits (2|4)")
+    ap.add_argument("--k-group", type=int, default=0, help="override G for keys (32|64|128 tokens)")
+    ap.add_argument("--v-group", type=int, default=0, help="override G for values (32|64|128 channels)")
     ap.add_argument("--splits", type=int, default=0, help="override the split-K factor")
     ap.add_argument("--context", type=int, default=0, help="override the context length (multiple of 128)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size")
@@ -115,6 +117,9 @@ def main():
     w = synth.CONFIGS[args.workload]
     if args.bits:
         w = w.replace(bits=args.bits)
+    if args.k_group or args.v_group:
+        w = w.replace(k_group=args.k_group or w.k_group, v_group=args.v_group or w.v_group,
+                      name="%s-gk%d-gv%d" % (w.name, args.k_group or w.k_group, args.v_group or w.v_group))
     if args.context or args.batch:
         w = w.replace(context=args.context or w.context, batch=args.batch or w.batch,
                       name="%s-b%d-s%d" % (w.name, args.batch or w.batch, args.context or w.context))

@@ -362,7 +362,10 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     uint4 mn, mx;   // packed fp16, the 8 channels of a channel group
   };
   __shared__ __align__(16) MinMax s_red[NGK][4][16];   // [group][wave][channel group]
-  __shared__ __align__(16) float4 s_par[NGK][D];       // per channel: 1/Delta, -z, qmax-z, z*place
+  // per channel: 1/Delta, -z, qmax-z, z*place; channel 8*cg + e sits at slot 16*e + cg, so the
+  // 16 lanes of a row (cg = 0..15) read 256 consecutive bytes (channel order would put them
+  // 128 bytes apart: an 8-way bank conflict on every read)
+  __shared__ __align__(16) float4 s_par[NGK][D];
   __shared__ __align__(16) uint8_t s_kimg[IMG];        // key-code page image
   // value-code page image, staged with 64 bytes of padding after every eighth of the image:
   // the lanes of a wave write pieces that are 1/8, 1/4 and 1/2 image apart, which would
@@ -578,7 +581,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       quant_params<META, BITS>(half_of(mnw, e & 1), half_of(mxw, e & 1), zp_min, df, rd, z);
       // place value of this channel's code inside its packed word (4-bit: two 16-bit halves)
       const float place = ldexpf(1.0f, BITS * ((BITS == 2) ? e : (e & 3)));
-      s_par[gk][c] = zp_min ? make_float4(rd, z, 0.0f, 0.0f)
+      s_par[gk][16 * e + cg] = zp_min ? make_float4(rd, z, 0.0f, 0.0f)
                             : make_float4(rd, -z, QMAX - z, z * place);
       const int pos = kmeta_pos_of_chan(BITS, c);
       o_kmeta[(size_t)gk * D + pos] = from_f32<META>(df);
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     float rd[8], lo[8], hi[8], zs0 = 0.0f, zs1 = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float4 q = s_par[gk][8 * cg + e];
+      const float4 q = s_par[gk][16 * e + cg];
       rd[e] = q.x;
       lo[e] = q.y;
       hi[e] = q.z;

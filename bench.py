@@ -202,11 +202,19 @@ def measure(args, w, np, torch, ob, synth):
     EV_EVERY = 5   # every 5th launch of the decode kernel carries a HIP event pair (5 is
                    # coprime to the usual copy counts, so every cache copy gets sampled)
 
+    dbg = os.environ.get("OSCAR_BENCH_DEBUG")
+
     def step(i, ev=None):
         c = caches[i % n_copies]
+        ta = time.perf_counter()
         ob.quantize_append(c, new_k[i], new_v[i], stream=stream)
+        tb = time.perf_counter()
         ob.decode_attn_partial(c, q, ws, splits, stream=stream, timer=ev)
+        tc = time.perf_counter()
         ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
+        if dbg and time.perf_counter() - ta > 2e-3:
+            print("slow step", i, "append %.1f partial %.1f reduce %.1f ms" % (
+                (tb - ta) * 1e3, (tc - tb) * 1e3, (time.perf_counter() - tc) * 1e3), file=sys.stderr)
 
     # the first event-carrying launch of a process pays a one-time host cost (tens of ms when
     # the previous process's memory is still being reclaimed): take it in the warm-up
@@ -219,6 +227,9 @@ def measure(args, w, np, torch, ob, synth):
     warm_ev.close()
     evs = [ob.Timer() if i % EV_EVERY == 0 or args.steps < 64 else None for i in range(args.steps)]
     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(stream)       # events are created at their first record: keep that, and whatever
+    g1.record(stream)       # else a first use costs on the host, outside the timed region
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     g0.record(stream)
     hts = []

@@ -43,8 +43,8 @@ LLC_BYTES = 256 << 20       # Infinity Cache
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=512)
-    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--steps", type=int, default=2048)
+    ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations")
     ap.add_argument("--bits", type=int, default=0, help="override bits (2|4)")
     ap.add_argument("--k-group", type=int, default=0, help="override G for keys (32|64|128 tokens)")

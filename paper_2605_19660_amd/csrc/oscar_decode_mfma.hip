@@ -293,18 +293,28 @@ template <int BITS, int NGV> struct ValRegs {
 };
 
 // Eight consecutive values of the caller's dtype (a run-time property here), held raw.
+// Loads are buffer loads without branches: a branch around a load makes the compiler wait
+// for every load in flight where the branches join (the start of this kernel was a chain of
+// such waits: each residual token's loads completed, behind the whole first page, before the
+// next token's were issued).  fp32 needs 32 bytes; the upper 16 come through a second
+// resource that is void for the 16-bit types.
+struct IoRsrc {
+  __amdgpu_buffer_rsrc_t lo, hi;
+  int es;   // bytes per element
+  __device__ __forceinline__ void make(const void* base, size_t first_elem, int n_elem, int dt,
+                                       bool valid) {
+    es = dt == OSCAR_F32 ? 4 : 2;
+    uint8_t* p = const_cast<uint8_t*>(static_cast<const uint8_t*>(base)) + first_elem * (size_t)es;
+    lo = __builtin_amdgcn_make_buffer_rsrc(p, 0, valid ? n_elem * es : 0, 0x00020000);
+    hi = __builtin_amdgcn_make_buffer_rsrc(p, 0, (valid && dt == OSCAR_F32) ? n_elem * es : 0, 0x00020000);
+  }
+};
 struct Raw8rt {
   uint4 a, b;
-  __device__ __forceinline__ void zero() { a = b = make_uint4(0u, 0u, 0u, 0u); }
-  __device__ __forceinline__ void load(const void* p, size_t idx, int dt) {
-    if (dt == OSCAR_F32) {
-      const uint4* vp = reinterpret_cast<const uint4*>(static_cast<const float*>(p) + idx);
-      a = vp[0];
-      b = vp[1];
-    } else {
-      a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + idx);
-      b = a;
-    }
+  // elements elem .. elem+7 of the resource (zeros past its end)
+  __device__ __forceinline__ void load(const IoRsrc& r, int elem) {
+    a = buf_load16(r.lo, elem * r.es);
+    b = buf_load16(r.hi, elem * r.es + 16);
   }
   __device__ __forceinline__ void widen(float (&x)[8], int dt) const {
     if (dt == OSCAR_F32) {
@@ -323,31 +333,34 @@ struct Raw8rt {
   }
 };
 
+// The residual window of one (sequence, kv head) as buffer resources: K_u (fp16), V (caller's
+// dtype), token norms (fp16 here: this kernel requires fp16 metadata); void when the wave has
+// no residual token.
+struct ResRsrc {
+  __amdgpu_buffer_rsrc_t k, n;
+  IoRsrc v;
+  __device__ __forceinline__ void make(const DecodeParams& P, size_t rb, bool valid) {
+    uint8_t* kp = const_cast<uint8_t*>(static_cast<const uint8_t*>(P.c.res_k)) + rb * D * 2;
+    uint8_t* np = const_cast<uint8_t*>(static_cast<const uint8_t*>(P.c.res_norm)) + rb * 2;
+    k = __builtin_amdgcn_make_buffer_rsrc(kp, 0, valid ? R * D * 2 : 0, 0x00020000);
+    n = __builtin_amdgcn_make_buffer_rsrc(np, 0, valid ? R * 2 : 0, 0x00020000);
+    v.make(P.c.res_v, rb * D, R * D, P.c.cfg.io_dtype, valid);
+  }
+};
+
 // One residual token's share for a lane: 8 channels (channel group cg) of K_u (fp16) and of
 // V (caller's dtype), and the token norm, held raw until the query rotation is done.
+// `tok` is the token's slot in the window, clamped by the caller to a slot that exists.
 struct ResTok {
   uint4 k;
   Raw8rt v;
   uint32_t nrm;
-  __device__ __forceinline__ void load(const DecodeParams& P, const __half* rk, size_t rb, int t_lo,
-                                       int t, int rcount, int cg) {
-    k = make_uint4(0u, 0u, 0u, 0u);
-    v.zero();
-    nrm = 0u;
-    if (t < rcount) {   // wave-uniform
-      const size_t tok = rb + t_lo + t;
-      k = *reinterpret_cast<const uint4*>(rk + (size_t)(t_lo + t) * D + 8 * cg);
-      v.load(P.c.res_v, tok * D + 8 * cg, P.c.cfg.io_dtype);
-      if (P.g.meta_bytes == 4) nrm = static_cast<const uint32_t*>(P.c.res_norm)[tok];
-      else nrm = static_cast<const uint16_t*>(P.c.res_norm)[tok];
-    }
+  __device__ __forceinline__ void load(const ResRsrc& r, int tok, int cg) {
+    k = buf_load16(r.k, (tok * D + 8 * cg) * 2);
+    v.load(r.v, tok * D + 8 * cg);
+    nrm = (uint32_t)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r.n, tok * 2, 0, 0);
   }
 };
-__device__ __forceinline__ float load_meta_bits(uint32_t bits, int meta_bytes) {
-  if (meta_bytes == 4) return __uint_as_float(bits);
-  return __half2float(__ushort_as_half((unsigned short)bits));
-}
-
 // Step sizes are non-negative fp16 numbers, which order like their bit patterns: packed
 // unsigned 16-bit max needs no NaN canonicalization.
 typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
@@ -425,12 +438,11 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   // channels (channel group cg) per lane; absent heads read as zeros
   const int cg = channel_group_of_row_lane(n);
   Raw8rt qraw[HP];
+  {
+    IoRsrc qr_;   // the group's gq query vectors; heads past gq fall off its end and read zeros
+    qr_.make(P.q, ((size_t)b * Hq + (size_t)kvh * gq) * D, gq * D, P.c.cfg.io_dtype, true);
 #pragma unroll
-  for (int s = 0; s < HP; ++s) {
-    const int h = q4 + 4 * s;
-    qraw[s].zero();
-    if (h < gq)
-      qraw[s].load(P.q, ((size_t)b * Hq + (size_t)kvh * gq + h) * D + 8 * cg, P.c.cfg.io_dtype);
+    for (int s = 0; s < HP; ++s) qraw[s].load(qr_, (q4 + 4 * s) * D + 8 * cg);
   }
 
   const int seq_len = P.c.seq_lens[b];
@@ -452,11 +464,13 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     kr.load(first, lane);
     vr.load(first, lane);
   }
-  const size_t rb = ((size_t)b * Hkv + kvh) * R;
-  const __half* rk = reinterpret_cast<const __half*>(P.c.res_k) + rb * D;
+  ResRsrc rres;
+  rres.make(P, ((size_t)b * Hkv + kvh) * R, wave_res);
+  // slot of the wave's token i of pass p0, clamped to the slice (masked where it is used)
+  auto res_slot = [&](int p0, int i) { return t_lo + max(0, min(p0 + 4 * wave + i, rcount - 1)); };
   ResTok rt_first[4];   // the wave's four tokens of the first residual pass
 #pragma unroll
-  for (int i = 0; i < 4; ++i) rt_first[i].load(P, rk, rb, t_lo, 4 * wave + i, rcount, cg);
+  for (int i = 0; i < 4; ++i) rt_first[i].load(rres, res_slot(0, i), cg);
 
   // this wave's operand tables start as zeros (rows of absent heads stay zero)
   for (int i = lane; i < 16 * TABW / 8; i += 64) {
@@ -509,12 +523,12 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         ResTok rt = rt_first[i];
-        if (p0 > 0) rt.load(P, rk, rb, t_lo, p0 + 4 * wave + i, rcount, cg);
+        if (p0 > 0) rt.load(rres, res_slot(p0, i), cg);
         const bool valid = p0 + 4 * wave + i < rcount;   // wave-uniform
         float kv[8];
         halves_to_f32(rt.k, kv);
         rt.v.widen(vv[i], P.c.cfg.io_dtype);
-        const float nrm = load_meta_bits(rt.nrm, P.g.meta_bytes);
+        const float nrm = __half2float(__ushort_as_half((unsigned short)rt.nrm));
 #pragma unroll
         for (int s = 0; s < HP; ++s) {
           float acc = qh[s][0] * kv[0];

@@ -93,3 +93,25 @@ def test_split_heuristic_and_host_side_argument_checks_of_the_aids():
     assert L.oscar_timer_destroy(None) == ob.OK
     assert L.oscar_bf16_decode_attn(None, None, None, None, None, ob.BF16, ob.F32, 1, 128, 0, 8, 2, 128,
                                     0.0, 0, 1, None, 0, None) == ob.ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N above 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No CPU fallback: with no HIP library at the configured path the binding raises."""
+    import importlib
+    monkeypatch.setenv("OSCAR_HIP_LIB", "/nonexistent/liboscar_hip.so")
+    mod = importlib.reload(importlib.import_module("paper_2605_19660_amd.binding"))
+    try:
+        with pytest.raises(ImportError):
+            mod.lib()
+    finally:
+        monkeypatch.delenv("OSCAR_HIP_LIB")
+        importlib.reload(mod)

@@ -202,19 +202,11 @@ def measure(args, w, np, torch, ob, synth):
     EV_EVERY = 5   # every 5th launch of the decode kernel carries a HIP event pair (5 is
                    # coprime to the usual copy counts, so every cache copy gets sampled)
 
-    dbg = os.environ.get("OSCAR_BENCH_DEBUG")
-
     def step(i, ev=None):
         c = caches[i % n_copies]
-        ta = time.perf_counter()
         ob.quantize_append(c, new_k[i], new_v[i], stream=stream)
-        tb = time.perf_counter()
         ob.decode_attn_partial(c, q, ws, splits, stream=stream, timer=ev)
-        tc = time.perf_counter()
         ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
-        if dbg and time.perf_counter() - ta > 2e-3:
-            print("slow step", i, "append %.1f partial %.1f reduce %.1f ms" % (
-                (tb - ta) * 1e3, (tc - tb) * 1e3, (time.perf_counter() - tc) * 1e3), file=sys.stderr)
 
     # the first event-carrying launch of a process pays a one-time host cost (tens of ms when
     # the previous process's memory is still being reclaimed): take it in the warm-up
@@ -232,15 +224,9 @@ def measure(args, w, np, torch, ob, synth):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     g0.record(stream)
-    hts = []
     for i in range(args.steps):
         step(args.warmup + i, evs[i])
-        hts.append(time.perf_counter())
     g1.record(stream)
-    if os.environ.get("OSCAR_BENCH_DEBUG"):
-        d = np.diff(np.array([t0] + hts)) * 1e6
-        print("enqueue us: first", d[:8].round(1), "max", d.max().round(1), "at", int(d.argmax()),
-              "big", [(int(i), float(x.round(0))) for i, x in enumerate(d) if x > 500], file=sys.stderr)
     t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0

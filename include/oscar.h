@@ -196,9 +196,9 @@ int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t
  *   num_splits : split-K factor over the sequence (<= 512), 0 = oscar_decode_auto_splits
  *   workspace  : device scratch of at least oscar_decode_workspace_bytes(...)
  * A sequence with seq_lens[b] == 0 yields zeros.
- * Two kernels sit behind this call: the matrix-core one (fp16 metadata; (k_group, v_group) in
- * {(128,32), (32,32), (128,128)}; scale_mode L2 or MAX, i.e. keys scaled into [-1, 1]) and a
- * generic plain-ALU one for every other configuration; both are checked against the same
+ * Two kernels sit behind this call: the matrix-core one (fp16 metadata; scale_mode L2 or MAX,
+ * i.e. keys scaled into [-1, 1]) and a generic plain-ALU one for every other configuration
+ * (fp32 metadata; scale_mode NONE or MEAN_ABS); both are checked against the same
  * oracle.  The environment variable OSCAR_DECODE_PATH=generic (read at every call) forces
  * the generic kernel; it exists for tests and profiling. */
 int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_t out_dtype,

@@ -150,7 +150,9 @@ void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int 
 // Resident workgroups per CU of the matrix-core decode kernel for a variant (bits, head slots,
 // key groups per page, value groups); the launch bounds and the split heuristic share it.
 __host__ __device__ constexpr int oscar_decode_mfma_wgs_per_cu(int bits, int hp, int ngk, int ngv) {
-  return hp == 1 ? ((bits == 4 && ngk == 4) ? 1 : 2) : ((ngk == 1 && (bits == 2 || ngv == 1)) ? 2 : 1);
+  if (hp == 1) return (bits == 4 && (ngk == 4 || (ngk == 2 && ngv == 4))) ? 1 : 2;
+  if (bits == 2) return (ngv == 4 && ngk >= 2) ? 1 : 2;
+  return (ngv == 1 && ngk <= 2) ? 2 : 1;
 }
 int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
                              hipEvent_t e0, hipEvent_t e1);

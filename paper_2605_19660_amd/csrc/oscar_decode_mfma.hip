@@ -384,11 +384,10 @@ __device__ __forceinline__ int row_hi(int h) { return 4 * (h & 3) + 2 * (h >> 2)
 
 // HP = head slots per accumulator lane group: 1 for up to 4 query heads per kv head, 2 for
 // 5..8 (twice the per-head registers).  Two workgroups per CU wherever the registers allow it
-// with little or no scratch memory: the one-slot variants except 4-bit codes with four key
-// groups per page, and the two-slot variants with one key group per page and 2-bit codes or
-// one value group; the rest run one workgroup per CU (their overflow then lives in
-// accumulation registers; measured: 4-bit, G_k = 32 took 188 us with 65 spilled registers at
-// two per CU and 76 us at one).
+// with little or no scratch memory (oscar_decode_mfma_wgs_per_cu lists the variants); the
+// rest run one workgroup per CU and their overflow lives in accumulation registers
+// (measured: 4-bit, G_k = 32 took 188 us with 65 spilled registers at two per CU, 76 us at
+// one).
 __host__ __device__ constexpr int decode_mfma_wgs_per_cu(int bits, int hp, int ngk, int ngv) {
   return oscar_decode_mfma_wgs_per_cu(bits, hp, ngk, ngv);
 }
@@ -927,6 +926,12 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipE
   OSCAR_MFMA_CASE(1, 4)
   OSCAR_MFMA_CASE(4, 4)
   OSCAR_MFMA_CASE(1, 1)
+  OSCAR_MFMA_CASE(2, 2)
+  OSCAR_MFMA_CASE(1, 2)
+  OSCAR_MFMA_CASE(2, 1)
+  OSCAR_MFMA_CASE(2, 4)
+  OSCAR_MFMA_CASE(4, 1)
+  OSCAR_MFMA_CASE(4, 2)
 #undef OSCAR_MFMA_CASE
   return OSCAR_ERR_UNSUPPORTED;
 }
@@ -934,7 +939,7 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipE
 }  // namespace
 
 // Launches the matrix-core partial pass when the configuration is one it is built for
-// (fp16 metadata; group sizes (128,32), (32,32) or (128,128); keys scaled into [-1, 1]); OSCAR_ERR_UNSUPPORTED
+// (fp16 metadata; group sizes 32, 64 or 128 on either side; keys scaled into [-1, 1]); OSCAR_ERR_UNSUPPORTED
 // tells the caller to use the generic kernel.
 int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
                              hipEvent_t e0, hipEvent_t e1) {

@@ -339,6 +339,27 @@ def test_decode_custom_softmax_scale(path, scale, monkeypatch):
         assert_decode_close(outp, oracle.plain_attn(q, k, v, scale=scale))
 
 
+@pytest.mark.parametrize("gq", [4, 7])
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("kg,vg", [(128, 32), (128, 64), (128, 128), (64, 32), (64, 64), (64, 128),
+                                   (32, 32), (32, 64), (32, 128)])
+def test_decode_every_group_size_combination(kg, vg, bits, gq):
+    """All nine (G_k, G_v) pairs x INT2/INT4 x one and two head slots per lane group run on the
+    matrix-core kernel: encoder bit-exact, decode within tolerance, with a non-empty residual
+    and two splits."""
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=2 * gq, n_kv_heads=2, context=128 * 5 + 70,
+                                  bits=bits, k_group=kg, v_group=vg)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    g, o = make_pair(w, 8)
+    ob.quantize_append(g, to_dev(k, w.io_dtype), to_dev(v, w.io_dtype), eager=True, max_seq_len_hint=0)
+    o.append(k, v, eager=True)
+    assert_cache_equal(g, o, w)
+    out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=w.context, num_splits=2)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 def test_decode_long_stream_one_split_crosses_block_table_chunks(bits):
     """One split over 300 pages: every wave walks 75 pages, more than the 64 block-table entries

@@ -180,7 +180,11 @@ size_t oscar_decode_workspace_bytes(const oscar_config *cfg, int32_t batch, int3
  *              residual through the attention that follows (the algorithm attends
  *              before it flushes) and is quantized by the next append.
  * Updates seq_lens / res_lens on the device. Residual keys are quantized from
- * their stored fp16 values (no second rotation). */
+ * their stored fp16 values (no second rotation). A sequence that receives no token
+ * (T == 0 or new_lens[b] == 0) is left untouched under either rule.
+ * One launch (plus the length-update launch without cache->tickets); with
+ * OSCAR_NORM_ALL_KV_HEADS a launch in front computes the norms of the new tokens that
+ * move into pages and parks them in those pages' norm slots. */
 int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t *new_lens,
                           oscar_cache *cache, int32_t max_seq_len_hint, uint32_t flags,
                           void *stream);

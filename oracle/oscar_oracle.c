@@ -52,6 +52,9 @@
  *   - max == min: Delta := |min| (1 if that is 0), so a constant group
  *     round-trips exactly.
  *   - zero-norm token: K_u = 0.
+ *   - a parameter (Delta, z, n) beyond the largest finite value of its storage type is
+ *     stored as that value (saturation); K_u is then K_h over the saturated norm, so
+ *     n * K_u still restores K_h.
  *   - mean absolute value: |x_j| summed in the same balanced tree as the squared
  *     sum, times 1/d.
  *   - norm over all kv heads: the per-head squared sums (each in its tree
@@ -139,6 +142,19 @@ float oref_round_dtype(float f, int dtype) {
   return f;
 }
 
+/* Metadata (Delta, zero-point, token norm) is stored in `dtype` [Fmt]; a value beyond the
+ * largest finite number of that type is stored as that number (saturation), so that no
+ * stored parameter is ever infinite and the decode stays finite.  The paper is silent on
+ * metadata overflow; an fp32 store is unchanged. */
+float oref_round_meta(float f, int dtype) {
+  float r = oref_round_dtype(f, dtype);
+  if (isinf(r) && !isinf(f)) {
+    float big = (dtype == OREF_F16) ? 65504.0f : 3.3895313892515355e38f;
+    r = (f > 0) ? big : -big;
+  }
+  return r;
+}
+
 /* ------------------------------------------------------------------------ */
 /* Canalized Rotation [Key-xf]: x <- H_d x / sqrt(d), Sylvester Hadamard.    */
 /* Butterfly stages h = 1,2,4,...,d/2; pair (i, i|h): (a,b) -> (a+b, a-b).   */
@@ -201,7 +217,7 @@ void oref_key_transform(const float *k, int d, int rotate, int scale_mode,
     } else {                                            /* [Abl] mean_j |x_j| */
       n = oref_sumabs_tree(x, d) * (1.0f / (float)d);
     }
-    nf = oref_round_dtype(n, meta_dtype);
+    nf = oref_round_meta(n, meta_dtype);
     float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
     for (int j = 0; j < d; ++j) x[j] = x[j] * inv;
   }
@@ -222,7 +238,7 @@ float oref_token_norm_all_heads(const float *k_heads, int n_heads, size_t head_s
     float sh = oref_sumsq_tree(x, d);
     s = (h == 0) ? sh : s + sh;
   }
-  return oref_round_dtype(sqrtf(s), meta_dtype);
+  return oref_round_meta(sqrtf(s), meta_dtype);
 }
 
 /* Key transform of one head vector with a norm that was computed elsewhere (nf, already
@@ -251,15 +267,15 @@ void oref_quant_params(float mn, float mx, int bits, int meta_dtype, int zp_mode
                        float *delta, float *zero) {
   float qmax = (float)((1 << bits) - 1);
   float dl = (mx - mn) / qmax;
-  float df = oref_round_dtype(dl, meta_dtype);
+  float df = oref_round_meta(dl, meta_dtype);
   if (df == 0.0f) {                       /* constant (or underflowing) group */
-    df = oref_round_dtype(fabsf(mn), meta_dtype);
+    df = oref_round_meta(fabsf(mn), meta_dtype);
     if (df == 0.0f || isinf(df)) df = 1.0f;
   }
   float rd = 1.0f / df;
   float z;
-  if (zp_mode == OREF_ZP_INT) z = oref_round_dtype(rintf(-mn * rd), meta_dtype);
-  else z = oref_round_dtype(mn, meta_dtype);
+  if (zp_mode == OREF_ZP_INT) z = oref_round_meta(rintf(-mn * rd), meta_dtype);
+  else z = oref_round_meta(mn, meta_dtype);
   *delta = df;
   *zero = z;
 }

@@ -53,6 +53,10 @@ def lib():
         fp = C.POINTER(C.c_float)
         L.oref_round_dtype.restype = C.c_float
         L.oref_round_dtype.argtypes = [C.c_float, C.c_int]
+        L.oref_round_meta.restype = C.c_float
+        L.oref_round_meta.argtypes = [C.c_float, C.c_int]
+        L.oref_sumabs_tree.restype = C.c_float
+        L.oref_sumabs_tree.argtypes = [fp, C.c_int]
         L.oref_fwht.argtypes = [fp, C.c_int]
         L.oref_sumsq_tree.restype = C.c_float
         L.oref_sumsq_tree.argtypes = [fp, C.c_int]
@@ -95,6 +99,11 @@ def round_dtype(x: float, dtype: int) -> float:
     return float(lib().oref_round_dtype(C.c_float(x), dtype))
 
 
+def round_meta(x: float, dtype: int) -> float:
+    """Storage rounding of a metadata value: nearest even, saturating at the largest finite value."""
+    return float(lib().oref_round_meta(C.c_float(x), dtype))
+
+
 def fwht(x) -> np.ndarray:
     """Normalized Sylvester Hadamard transform of the last axis."""
     y = _f32(x).copy()
@@ -107,6 +116,11 @@ def fwht(x) -> np.ndarray:
 def sumsq_tree(x) -> float:
     y = _f32(x)
     return float(lib().oref_sumsq_tree(_fp(y), y.shape[0]))
+
+
+def sumabs_tree(x) -> float:
+    y = _f32(x)
+    return float(lib().oref_sumabs_tree(_fp(y), y.shape[0]))
 
 
 def key_transform(k, rotate=1, scale_mode=SCALE_L2, meta_dtype=F32):

@@ -98,6 +98,24 @@ def test_sumsq_tree_value_and_order():
     assert np.float32(got) == t[0]
 
 
+def test_sumabs_tree_value_and_order():
+    """The mean-absolute-value coefficient sums |x_j| in the same balanced tree as the squared
+    sum: adjacent pairs first, written out independently in fp32 by pairwise halving."""
+    rng = np.random.default_rng(8)
+    x = (rng.standard_normal(128) * 3).astype(np.float32)
+    got = oracle.sumabs_tree(x)
+    assert np.isclose(got, float(np.abs(x.astype(np.float64)).sum()), rtol=1e-6)
+    t = np.abs(x).astype(np.float32)
+    while t.shape[0] > 1:
+        t = (t[0::2] + t[1::2]).astype(np.float32)
+    assert np.float32(got) == t[0]
+    # a left-to-right running sum differs in the last bits on this input: the order is pinned
+    seq = np.float32(0)
+    for v in np.abs(x):
+        seq = np.float32(seq + v)
+    assert seq != t[0]
+
+
 # ---------------------------------------------------------- token scaling ---
 
 def test_worked_example_of_scaling_artifact():
@@ -138,6 +156,53 @@ def test_key_transform_unit_norm_and_restoration(meta):
 def test_zero_token_gives_zero_direction():
     u, n = oracle.key_transform(np.zeros(128, np.float32), meta_dtype=F16)
     assert n == 0.0 and not u.any()
+
+
+def test_metadata_saturates_at_the_largest_finite_value():
+    """Stored parameters are never infinite: a value past the largest finite number of the
+    storage type is stored as that number (fp16: 65504); in-range values round to nearest even
+    exactly as numpy does; fp32 storage is untouched."""
+    for x, want in ((65504.0, 65504.0), (65519.9, 65504.0), (65520.0, 65504.0), (1e6, 65504.0),
+                    (-65520.0, -65504.0), (-3e38, -65504.0), (0.1, float(np.float16(0.1))),
+                    (2049.0, 2048.0), (2051.0, 2052.0), (-4097.0, -4096.0)):
+        assert oracle.round_meta(x, F16) == want, x
+    assert oracle.round_meta(1e6, F32) == 1e6 and oracle.round_meta(3e38, F32) == np.float32(3e38)
+
+
+def test_token_norm_beyond_fp16_range_saturates_and_still_restores_the_key():
+    """A token whose norm exceeds 65504 with fp16 metadata: the stored norm is 65504, K_u is
+    K_h over the stored norm (so its length exceeds one), everything stays finite and
+    n * K_u still restores the rotated key to fp16 accuracy.  Just inside the range nothing
+    changes."""
+    rng = np.random.default_rng(31)
+    H = hadamard_closed_form(128)
+    for target in (65000.0, 70000.0, 3.0e5):
+        k = rng.standard_normal(128)
+        k = (k / np.linalg.norm(k) * target).astype(np.float32)
+        kh = H @ k.astype(np.float64)
+        u, n = oracle.key_transform(k, meta_dtype=F16)
+        true_n = np.linalg.norm(k.astype(np.float64))
+        assert np.isfinite(u).all() and np.isfinite(n)
+        assert n == (65504.0 if true_n >= 65520 else float(np.float16(true_n)))
+        assert np.abs(u.astype(np.float64) * n - kh).max() <= np.abs(kh).max() * 2.0 ** -11 * 1.05
+        assert abs(np.linalg.norm(u.astype(np.float64)) - true_n / n) < 3e-3 * true_n / n
+        # the all-heads norm follows the same rule
+        n2 = oracle.token_norm_all_heads(np.stack([k, k]), meta_dtype=F16)
+        assert n2 == min(65504.0, float(np.float16(min(true_n * np.sqrt(2.0), 65504.0))))
+    # in a cache: the decode stays finite and, at 8 bits, equals textbook attention
+    w = synth.TINY.replace(context=160)
+    kk, vv = synth.make_kv_batch(w)
+    kk = kk.copy()
+    kk[0, 5, 0] *= np.float32(7.0e4 / np.linalg.norm(kk[0, 5, 0]))
+    kk[0, 140, 0] *= np.float32(1.0e5 / np.linalg.norm(kk[0, 140, 0]))     # one in a page, one in the residual
+    q = synth.make_q(w) * np.float32(1e-3)                                  # keep the logits moderate
+    c = OracleCache(OracleConfig(128, 8, 128, 32, 128, F16), 1, 1, 256)
+    c.append(kk, vv, eager=True)
+    assert c.k_norm[0, 0, 5] == 65504.0 and c.res_norm[0, 0, 140 - 128] == 65504.0
+    got = c.decode_attn(q)
+    assert np.isfinite(got).all()
+    ref = full_precision_attention(q, kk, vv, 1)
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) < 3e-2
 
 
 # ---------------------------------- alternative scaling coefficients --
@@ -331,6 +396,57 @@ def test_ties_round_to_even():
     assert oracle.quant_code(2.5, 1.0, 0.0, 2) == 2
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_large_integer_zero_point_is_stored_rounded_and_used_as_stored(bits):
+    """Eq. 3-4 with fp16 parameters on a nearly constant group far from zero: z = round(-min/Delta)
+    exceeds 2048, where fp16 no longer holds every integer.  The stored z is the fp16 rounding of
+    the integer, the codes are computed with the stored value, they stay in range, and the
+    reconstruction error is bounded by Delta/2 plus Delta times the storage error of z.  With
+    fp32 parameters the same group keeps the plain Delta/2 bound."""
+    qmax = 2 ** bits - 1
+    rng = np.random.default_rng(77 + bits)
+    for base, width in ((0.5, 0.00049), (100.0, 0.03), (-37.0, 0.004), (3000.0, 0.9)):
+        x = (base + width * rng.random(32)).astype(np.float32)
+        x[0], x[1] = np.float32(base), np.float32(base + width)
+        for meta in (F16, F32):
+            codes, delta, zero = oracle.quant_group(x, bits, meta, ZP_INT)
+            mn, mx = float(x.min()), float(x.max())
+            d_exact = (np.float32(mx) - np.float32(mn)) / np.float32(qmax)
+            if meta == F16:
+                assert delta == float(np.float16(d_exact)) and delta > 0
+                z_int = float(np.rint(np.float32(-mn) * (np.float32(1.0) / np.float32(delta))))
+                assert abs(z_int) > 2048
+                # stored rounded (spacing 2, 4, 8 ...), saturated past the fp16 range
+                want_z = float(np.float16(z_int)) if abs(z_int) < 65520 else float(np.copysign(65504.0, z_int))
+                assert zero == want_z
+            else:
+                z_int = zero
+                assert zero == round(zero)
+            assert codes.min() >= 0 and codes.max() <= qmax
+            xh = np.array([oracle.dequant(int(c), delta, zero, ZP_INT) for c in codes])
+            clamp_free = (codes > 0) & (codes < qmax)
+            lim = delta / 2 + delta * abs(z_int - zero) + 2e-7 * abs(base) * (1 + abs(z_int)) ** 0
+            assert np.abs(x - xh)[clamp_free].max(initial=0.0) <= lim * 1.001 + 1e-6 * abs(base)
+            # each code is what Eq. 3 gives with the stored parameters, evaluated independently
+            want = np.clip(np.rint(x * (np.float32(1.0) / np.float32(delta))) + np.float32(zero), 0, qmax)
+            assert np.array_equal(codes, want.astype(np.uint8))
+
+
+def test_parameters_that_overflow_fp16_saturate():
+    """A value group whose step exceeds 65504 (bf16 inputs can hold it): Delta is stored as
+    65504, z stays a finite integer, codes stay in range and the reconstruction is finite."""
+    x = np.array([-3.0e5, 1.0e5, 2.9e5, 0.0] * 8, np.float32)
+    codes, delta, zero = oracle.quant_group(x, 2, F16, ZP_INT)
+    assert delta == 65504.0 and np.isfinite(zero) and zero == round(zero)
+    assert codes.min() >= 0 and codes.max() <= 3
+    assert all(np.isfinite(oracle.dequant(int(c), delta, zero, ZP_INT)) for c in codes)
+    codes, delta, zero = oracle.quant_group(x, 2, F16, ZP_MIN)
+    assert delta == 65504.0 and zero == -65504.0 and codes.max() <= 3
+    # a constant group far outside the fp16 range: Delta := |min| saturated
+    codes, delta, zero = oracle.quant_group(np.full(32, 1.0e6, np.float32), 2, F16, ZP_INT)
+    assert delta == 65504.0 and np.isfinite(zero) and not codes.any()
+
+
 # --------------------------------------------------- grouping axes + cache --
 
 def _cache(bits=2, meta=F32, kg=128, vg=32, rotate=1, scale=SCALE_L2, zp=ZP_INT, B=1, H=1,
@@ -451,6 +567,68 @@ def full_precision_attention(q, k, v, g):
             p = np.exp(lg - lg.max())
             out[b, h] = (p / p.sum()) @ vv
     return out
+
+
+def textbook_attention(q, k, v, g, scale, lens=None):
+    """softmax(scale * q K^T) V in float64 on un-rotated K, V, with optional per-sequence lengths."""
+    B, Hq, d = q.shape
+    out = np.zeros((B, Hq, d))
+    for b in range(B):
+        n = k.shape[1] if lens is None else int(lens[b])
+        if n == 0:
+            continue
+        for h in range(Hq):
+            kk, vv = k[b, :n, h // g].astype(np.float64), v[b, :n, h // g].astype(np.float64)
+            lg = (kk @ q[b, h].astype(np.float64)) * scale
+            p = np.exp(lg - lg.max())
+            out[b, h] = (p / p.sum()) @ vv
+    return out
+
+
+@pytest.mark.parametrize("scale", [0.02, 0.2])
+def test_softmax_scale_override_against_textbook_attention(scale):
+    """softmax_scale > 0 replaces 1/sqrt(d): at 8 bits the decode oracle must agree with textbook
+    attention evaluated with that same scale, differ from the default-scale result, and
+    scale <= 0 must mean the default."""
+    w = synth.TINY.replace(batch=2, n_q_heads=4, n_kv_heads=2, context=300)
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    c = _cache(bits=8, B=2, H=2)
+    c.append(k, v, eager=True)
+    got = c.decode_attn(q, scale=scale)
+    want = textbook_attention(q, k, v, 2, scale)
+    assert np.abs(got - want).max() / np.abs(want).max() < 3e-2
+    default = c.decode_attn(q)
+    assert np.abs(default - want).max() / np.abs(want).max() > 0.1       # the scale matters here
+    assert np.array_equal(default, c.decode_attn(q, scale=0.0))
+    assert np.array_equal(default, c.decode_attn(q, scale=-1.0))
+    near = c.decode_attn(q, scale=float(np.float32(1.0 / np.sqrt(128.0))))
+    assert np.abs(near - default).max() <= 1e-6 * np.abs(default).max()
+    # the comparator oracle takes the same override
+    gotp = oracle.plain_attn(q, k, v, scale=scale)
+    assert np.allclose(gotp, want, rtol=1e-5, atol=1e-6 * np.abs(want).max())
+    assert np.array_equal(oracle.plain_attn(q, k, v), oracle.plain_attn(q, k, v, scale=-2.0))
+
+
+def test_plain_attention_oracle_with_sequence_lengths():
+    """seq_lens: every sequence attends to its first len tokens only; equal, bit for bit, to the
+    call on the truncated inputs, equal to textbook attention, and an empty sequence gives zeros."""
+    w = synth.TINY.replace(batch=3, n_q_heads=4, n_kv_heads=2, context=90, io_dtype="bf16")
+    k, v = synth.make_kv_batch(w)
+    q = synth.make_q(w)
+    lens = np.array([90, 0, 37], np.int32)
+    got = oracle.plain_attn(q, k, v, seq_lens=lens)
+    assert not got[1].any()
+    for b in (0, 2):
+        n = int(lens[b])
+        alone = oracle.plain_attn(q[b:b + 1], k[b:b + 1, :n], v[b:b + 1, :n])
+        assert np.array_equal(got[b], alone[0])
+    want = textbook_attention(q, k, v, 2, 1.0 / np.sqrt(128.0), lens)
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-6)
+    # tokens past the length must not matter
+    k2, v2 = k.copy(), v.copy()
+    k2[2, 37:], v2[2, 37:] = 1e3, -1e3
+    assert np.array_equal(oracle.plain_attn(q, k2, v2, seq_lens=lens)[2], got[2])
 
 
 def test_8bit_cache_reproduces_full_precision_attention():

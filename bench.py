@@ -353,8 +353,7 @@ def measure(args, w, np, torch, ob, synth):
         "step": "append 1 token/seq (1 launch) + decode attention (partial + reduce launches)",
                    "splits": splits, "cache_copies_rotated": n_copies},
         "roofline": {"bound": "hbm",
-                     "kernel": ("oscar_decode_mfma_kernel" if w.meta_dtype == "f16" and
-                                os.environ.get("OSCAR_DECODE_PATH", "")[:1] != "g"
+                     "kernel": ("oscar_decode_mfma_kernel" if w.meta_dtype == "f16"
                                 else "oscar_decode_partial_kernel") + " (split-K partial pass)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

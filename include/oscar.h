@@ -21,7 +21,8 @@
  *
  * Conventions
  *  - Every pointer named "device" is GPU memory owned by the caller; the library
- *    never allocates, frees or retains device memory and keeps no global state.
+ *    never allocates, frees or retains device memory.  Its only process-wide state is the
+ *    cached compute-unit count per device and the oscar_debug_force_generic_decode switch.
  *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
  *    the default stream). They do not synchronize and never read device memory
  *    on the host (oscar_debug_dump excepted), which is why upper bounds on
@@ -196,18 +197,24 @@ int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t
  *   q   : device, [batch][n_q_heads][head_dim], io_dtype
  *   out : device, [batch][n_q_heads][head_dim], out_dtype (OSCAR_F32 or io_dtype)
  *   softmax_scale : <= 0 means 1/sqrt(head_dim)
- *   max_seq_len_hint : upper bound on seq_lens[] (>= 1); sizes the launch
+ *   max_seq_len_hint : upper bound on seq_lens[] (>= 0; negative = OSCAR_ERR_INVALID_ARG);
+ *                only used to choose the split count when num_splits == 0 (0 gives one split)
  *   num_splits : split-K factor over the sequence (<= 512), 0 = oscar_decode_auto_splits
  *   workspace  : device scratch of at least oscar_decode_workspace_bytes(...)
  * A sequence with seq_lens[b] == 0 yields zeros.
  * Two kernels sit behind this call: the matrix-core one (fp16 metadata; scale_mode L2 or MAX,
  * i.e. keys scaled into [-1, 1]) and a generic plain-ALU one for every other configuration
  * (fp32 metadata; scale_mode NONE or MEAN_ABS); both are checked against the same
- * oracle.  The environment variable OSCAR_DECODE_PATH=generic (read at every call) forces
- * the generic kernel; it exists for tests and profiling. */
+ * oracle.  oscar_debug_force_generic_decode selects the generic kernel for every
+ * configuration; it exists for tests and profiling. */
 int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_t out_dtype,
                       float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Test / profiling switch: on != 0 makes every later decode launch of this process take the
+ * generic plain-ALU kernel, 0 restores the automatic choice.  Returns the previous setting.
+ * Host only, thread-safe (one atomic flag). */
+int oscar_debug_force_generic_decode(int32_t on);
 
 /* The two passes of oscar_decode_attn as separate calls, for callers that want to time
  * or overlap them: oscar_decode_attn(...) == partial(...) followed by reduce(...) on the

@@ -29,7 +29,8 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_decode_attn", "oscar_decode_attn_partial", "oscar_decode_attn_reduce",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
-           "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns")
+           "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns",
+           "oscar_debug_force_generic_decode")
 
 
 class OscarError(RuntimeError):
@@ -107,6 +108,8 @@ def lib():
     L.oscar_bf16_decode_attn.restype = C.c_int
     L.oscar_bf16_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32,
                                          f32, i32, i32, vp, sz, vp]
+    L.oscar_debug_force_generic_decode.restype = C.c_int
+    L.oscar_debug_force_generic_decode.argtypes = [i32]
     L.oscar_debug_dump.restype = C.c_int
     L.oscar_debug_dump.argtypes = [C.POINTER(CCache), i32, i32, i32] + [vp] * 11 + [vp]
     _lib = L
@@ -257,6 +260,11 @@ def decode_attn(cache: Cache, q, out=None, scale: float = 0.0, max_seq_len_hint:
                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(rc, "oscar_decode_attn")
     return out
+
+
+def debug_force_generic_decode(on: bool) -> bool:
+    """oscar_debug_force_generic_decode: route every decode launch to the plain-ALU kernel."""
+    return bool(lib().oscar_debug_force_generic_decode(1 if on else 0))
 
 
 class Timer:

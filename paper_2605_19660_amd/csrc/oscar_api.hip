@@ -2,6 +2,7 @@
 // debug dump that turns the packed page pools back into one code per byte.
 #include <string.h>
 
+#include <atomic>
 #include <vector>
 
 #include "oscar_common.h"
@@ -86,15 +87,32 @@ extern "C" size_t oscar_decode_workspace_bytes(const oscar_config* cfg, int32_t 
   return (size_t)batch * cfg->n_q_heads * num_splits * (cfg->head_dim + 2) * sizeof(float);
 }
 
+// Compute units of the current device, asked of the runtime once per device and process
+// (the attribute query is far cheaper than a full property read, and a decode step must not
+// pay either on every call).  256 (one MI355X) if the runtime cannot tell.
+static int compute_units_of_current_device() {
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> cached[kMaxDev];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  int v = 0;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+    (void)hipGetLastError();
+    v = 256;
+  }
+  cached[dev].store(v, std::memory_order_relaxed);
+  return v;
+}
+
 extern "C" int32_t oscar_decode_auto_splits(const oscar_config* cfg, int32_t batch,
                                             int32_t max_seq_len) {
   if (!cfg || batch <= 0 || cfg->n_kv_heads <= 0) return 1;
-  int n_cu = 256;
-  int dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-      prop.multiProcessorCount > 0)
-    n_cu = prop.multiProcessorCount;
+  const int n_cu = compute_units_of_current_device();
   const int pages = max_seq_len > 0 ? (max_seq_len + OSCAR_R - 1) / OSCAR_R : 1;
   const int units = batch * cfg->n_kv_heads;
   // two workgroups (8 waves) per CU are resident at a time (one for the register-hungry

@@ -28,6 +28,8 @@
 // images are built in LDS in their final page layout and leave with 16-byte stores.
 #pragma once
 #include "oscar_common.h"
+#include <type_traits>
+
 #include "oscar_rowops.h"
 
 struct AppendParams {
@@ -326,26 +328,38 @@ template <int BITS> __device__ __forceinline__ constexpr float place_value(int i
 
 // One token's 8 codes of a channel group -> one 16-bit (2-bit codes) or 32-bit (4-bit codes)
 // piece of chunk (tile = tok/16, n = tok%16, q4 = cg/4) of the key-code page image.
-template <bool ZPMIN, int BITS>
+// The code itself, clamp(rint(x * rd) + z, 0, qmax), from lo = -z: the form the packers take
+// when a zero-point is so large that sums of (code - z) * place would leave the range in which
+// fp32 holds every integer (|z| * 21845 < 2^24 for a word of eight 2-bit codes).
+template <int BITS> __device__ __forceinline__ float code_exact(float x, float rd, float lo) {
+  return __builtin_amdgcn_fmed3f(rintf(x * rd) - lo, 0.0f, (float)((1 << BITS) - 1));
+}
+// |z| up to this bound goes through the (code - z) form: every partial sum of a packed word
+// stays an exactly representable integer (2-bit: 512 * 21845, 4-bit: 512 * 4369 < 2^24)
+constexpr float kZeroPointFastBound = 512.0f;
+
+// EXACT: integer zero-points past kZeroPointFastBound (wave-uniform choice of the caller).
+template <bool ZPMIN, int BITS, bool EXACT>
 __device__ __forceinline__ void key_codes(const uint4& ku, const float (&rd)[8], const float (&lo)[8],
                                           const float (&hi)[8], float zs0, float zs1,
                                           uint8_t* s_kimg, int tok, int cg) {
   float x[8];
   widen_halves(ku, x);
   const int off = chunk_offset(BITS, tok / 16, tok % 16, cg / 4) + (cg % 4) * BITS;
+  auto term = [&](int e) {
+    return EXACT ? code_exact<BITS>(x[e], rd[e], lo[e]) : code_term<ZPMIN, BITS>(x[e], rd[e], lo[e], hi[e]);
+  };
   if (BITS == 2) {
-    float w = zs0;
+    float w = EXACT ? 0.0f : zs0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      w = fmaf(code_term<ZPMIN, BITS>(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w);
+    for (int e = 0; e < 8; ++e) w = fmaf(term(e), place_value<BITS>(e), w);
     *reinterpret_cast<uint16_t*>(&s_kimg[off]) = (uint16_t)(uint32_t)w;
   } else {
-    float w0 = zs0, w1 = zs1;
+    float w0 = EXACT ? 0.0f : zs0, w1 = EXACT ? 0.0f : zs1;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      w0 = fmaf(code_term<ZPMIN, BITS>(x[e], rd[e], lo[e], hi[e]), place_value<BITS>(e), w0);
-      w1 = fmaf(code_term<ZPMIN, BITS>(x[e + 4], rd[e + 4], lo[e + 4], hi[e + 4]),
-                place_value<BITS>(e), w1);
+      w0 = fmaf(term(e), place_value<BITS>(e), w0);
+      w1 = fmaf(term(e + 4), place_value<BITS>(e), w1);
     }
     *reinterpret_cast<uint32_t*>(&s_kimg[off]) = (uint32_t)w0 | ((uint32_t)w1 << 16);
   }
@@ -607,11 +621,22 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     if (zp_min) {
 #pragma unroll
       for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
-        key_codes<true, BITS>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
+        key_codes<true, BITS, false>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
     } else {
+      // a nearly constant channel far from zero has a huge integer zero-point: the wave then
+      // packs from the codes themselves (rare; the choice is uniform over the wave)
+      bool big = false;
 #pragma unroll
-      for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
-        key_codes<false, BITS>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
+      for (int e = 0; e < 8; ++e) big |= fabsf(lo[e]) > kZeroPointFastBound;
+      if (__any(big)) {
+#pragma unroll
+        for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
+          key_codes<false, BITS, true>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
+      } else {
+#pragma unroll
+        for (int p = gk * PPG; p < (gk + 1) * PPG; ++p)
+          key_codes<false, BITS, false>(ku[p], rd, lo, hi, zs0, zs1, s_kimg, p * 16 + slot, cg);
+      }
     }
   }
 
@@ -660,32 +685,42 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     float wv0[8], wv1[8], zv0 = 0.0f, zv1 = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) wv0[e] = wv1[e] = 0.0f;
+    // mode 0: integer zero-point, (code - z) form; 1: float zero-point; 2: integer zero-point
+    // past kZeroPointFastBound somewhere in the wave, the codes themselves
+    auto code_values = [&](auto mode_tag) {
+      constexpr int MODE = decltype(mode_tag)::value;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      float v[8];
-      vraw[p].widen(v);
-      const float rd = quad_bcast(prd[p & 1], p >> 1);
-      const float lo = quad_bcast(plo[p & 1], p >> 1);
-      const float hi = quad_bcast(phi[p & 1], p >> 1);
-      const float z = zp_min ? 0.0f : quad_bcast(pz[p & 1], p >> 1);
-      const float pl = place_value<BITS>(p >> 1);
-      float t[8];
-      if (zp_min) {
+      for (int p = 0; p < 8; ++p) {
+        float v[8];
+        vraw[p].widen(v);
+        const float rd = quad_bcast(prd[p & 1], p >> 1);
+        const float lo = quad_bcast(plo[p & 1], p >> 1);
+        const float hi = quad_bcast(phi[p & 1], p >> 1);
+        const float z = MODE == 0 ? quad_bcast(pz[p & 1], p >> 1) : 0.0f;
+        const float pl = place_value<BITS>(p >> 1);
+        float t[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = code_term<true, BITS>(v[e], rd, lo, hi);
-      } else {
+        for (int e = 0; e < 8; ++e)
+          t[e] = MODE == 1   ? code_term<true, BITS>(v[e], rd, lo, hi)
+                 : MODE == 2 ? code_exact<BITS>(v[e], rd, lo)
+                             : code_term<false, BITS>(v[e], rd, lo, hi);
+        if ((p & 1) == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = code_term<false, BITS>(v[e], rd, lo, hi);
+          for (int e = 0; e < 8; ++e) wv0[e] = fmaf(t[e], pl, wv0[e]);
+          zv0 = fmaf(z, pl, zv0);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) wv1[e] = fmaf(t[e], pl, wv1[e]);
+          zv1 = fmaf(z, pl, zv1);
+        }
       }
-      if ((p & 1) == 0) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wv0[e] = fmaf(t[e], pl, wv0[e]);
-        zv0 = fmaf(z, pl, zv0);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) wv1[e] = fmaf(t[e], pl, wv1[e]);
-        zv1 = fmaf(z, pl, zv1);
-      }
+    };
+    if (zp_min) {
+      code_values(std::integral_constant<int, 1>());
+    } else if (__any(fabsf(pz[0]) > kZeroPointFastBound || fabsf(pz[1]) > kZeroPointFastBound)) {
+      code_values(std::integral_constant<int, 2>());
+    } else {
+      code_values(std::integral_constant<int, 0>());
     }
     const int kk = slot >> 2, q4 = slot & 3;
 #pragma unroll

@@ -125,9 +125,15 @@ template <> __device__ __forceinline__ __hip_bfloat16 from_f32<__hip_bfloat16>(f
   return __float2bfloat16(x);
 }
 
-// round a float to the metadata storage type and widen it back
+// Round a float to the metadata storage type and widen it back.  A value beyond the largest
+// finite number of the type is stored as that number (no stored parameter is ever infinite):
+// clamping to +-65504 first gives exactly that, since everything in (65504, 65520) rounds down
+// to 65504 anyway.  fp32 storage is the identity.
 template <typename M> __device__ __forceinline__ float round_meta(float x) {
   return to_f32<M>(from_f32<M>(x));
+}
+template <> __device__ __forceinline__ float round_meta<__half>(float x) {
+  return __half2float(__float2half_rn(__builtin_amdgcn_fmed3f(x, -65504.0f, 65504.0f)));
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }

@@ -12,6 +12,8 @@
 // are built once per page, so logit = n_i * (sum_j A * c - bias); on the value side
 // w = Delta_v * c + (-Delta_v * z_v) is one fused multiply-add per element.
 // One workgroup serves all query heads of a kv head, so every packed byte is read once.
+#include <atomic>
+
 #include "oscar_decode_common.h"
 
 namespace {

@@ -30,7 +30,7 @@
 // tile is (token n, head group q4), which is also the lane that owns the 8-token operand
 // vector (k-step n/4, quarter n%4) of the P V contraction: probabilities go to LDS as
 // 16-byte vectors and come back as MFMA A-operands without any shuffle.
-#include <stdlib.h>
+#include <atomic>
 
 #include "oscar_decode_common.h"
 #include "oscar_rowops.h"
@@ -938,6 +938,14 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipE
 
 }  // namespace
 
+// Test / profiling switch of oscar_debug_force_generic_decode: the only process-wide state of
+// the library, one relaxed atomic flag read per launch.
+static std::atomic<int> g_force_generic{0};
+
+extern "C" int oscar_debug_force_generic_decode(int32_t on) {
+  return g_force_generic.exchange(on ? 1 : 0, std::memory_order_relaxed);
+}
+
 // Launches the matrix-core partial pass when the configuration is one it is built for
 // (fp16 metadata; group sizes 32, 64 or 128 on either side; keys scaled into [-1, 1]); OSCAR_ERR_UNSUPPORTED
 // tells the caller to use the generic kernel.
@@ -949,8 +957,7 @@ int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t 
   // maximum scaling); the un-scaled and mean-absolute-value ablations go to the generic kernel
   if (P.c.cfg.scale_mode != OSCAR_SCALE_L2 && P.c.cfg.scale_mode != OSCAR_SCALE_MAX)
     return OSCAR_ERR_UNSUPPORTED;
-  const char* force = getenv("OSCAR_DECODE_PATH");
-  if (force && force[0] == 'g') return OSCAR_ERR_UNSUPPORTED;  // "generic"
+  if (g_force_generic.load(std::memory_order_relaxed)) return OSCAR_ERR_UNSUPPORTED;
   if (P.g.bits == 2)
     return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st, e0, e1) : launch_groups<2, 2>(P, gq, grid, st, e0, e1);
   if (P.g.bits == 4)

@@ -24,3 +24,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _automatic_decode_kernel_choice_after_every_test():
+    """Tests that force the generic decode kernel must not leak the switch into later tests."""
+    yield
+    mod = sys.modules.get("paper_2605_19660_amd.binding")
+    if mod is not None and getattr(mod, "_lib", None) is not None:
+        mod.debug_force_generic_decode(False)

@@ -321,7 +321,7 @@ def test_decode_custom_softmax_scale(path, scale, monkeypatch):
     torch = _torch()
     ob = _ob()
     if path == "generic":
-        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+        _ob().debug_force_generic_decode(True)
     w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 4 + 33)
     k, v = synth.make_kv_batch(w)
     q = synth.make_q(w)
@@ -454,7 +454,7 @@ def test_decode_paths_and_fusion_agree_with_oracle(monkeypatch, path, fused, hq,
     into the append launch (ticket) or as a separate launch."""
     import torch
     ob = _ob()
-    monkeypatch.setenv("OSCAR_DECODE_PATH", path)
+    _ob().debug_force_generic_decode(path == "generic")
     w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=hq, n_kv_heads=hkv, context=128 * 6 + 100,
                                   bits=bits, k_group=kg, v_group=vg)
     k, v = synth.make_kv_batch(w)
@@ -488,7 +488,7 @@ def test_float_zero_point_mode_bitexact_and_decode(io, meta, bits, kg, vg, path,
     token-by-token appends included, and both decode kernels within tolerance."""
     ob = _ob()
     if path == "generic":
-        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+        _ob().debug_force_generic_decode(True)
     w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 3 + 61,
                                   io_dtype=io, meta_dtype=meta, bits=bits, k_group=kg, v_group=vg)
     k, v = synth.make_kv_batch(w)
@@ -555,7 +555,7 @@ def test_ablation_switches_bitexact_and_decode(rotation_off, scale, io, meta, bi
     others)."""
     ob = _ob()
     if path == "generic":
-        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+        _ob().debug_force_generic_decode(True)
     w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=128 * 2 + 77,
                                   io_dtype=io, meta_dtype=meta, bits=bits)
     k, v = synth.make_kv_batch(w)
@@ -584,7 +584,7 @@ def test_decode_step_replays_from_a_captured_graph(path, monkeypatch):
     torch = _torch()
     ob = _ob()
     if path == "generic":
-        monkeypatch.setenv("OSCAR_DECODE_PATH", "generic")
+        _ob().debug_force_generic_decode(True)
     n0, steps, splits = 128 * 2 + 100, 40, 3
     w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=n0 + steps)
     k, v = synth.make_kv_batch(w)

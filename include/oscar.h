@@ -211,6 +211,23 @@ int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_
                       float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  oscar_decode_attn with the
+ * split-K partials kept in a fixed buffer of OSCAR_NOALLOC_SCRATCH_BYTES inside the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends);
+ * same kernels, same results.  The call allocates and frees nothing.
+ *  - num_splits == 0 picks the split count as oscar_decode_attn does; a configuration whose
+ *    partials (oscar_decode_workspace_bytes) exceed the buffer returns OSCAR_ERR_WORKSPACE and
+ *    enqueues nothing (pass fewer splits, or use oscar_decode_attn with your own workspace).
+ *  - The first call on a device resolves the buffer's address (one runtime query, no
+ *    allocation); make that call once before starting a stream capture.
+ *  - All calls on one GPU share the one buffer: calls that overlap on different streams of the
+ *    same GPU race; serialize them.  Nothing has to be cleared between calls. */
+#define OSCAR_NOALLOC_SCRATCH_BYTES (4u << 20)
+int oscar_decode_attn_noalloc(const void *q, const oscar_cache *cache, void *out,
+                              int32_t out_dtype, float softmax_scale, int32_t max_seq_len_hint,
+                              int32_t num_splits, void *stream);
+
 /* Test / profiling switch: on != 0 makes every later decode launch of this process take the
  * generic plain-ALU kernel, 0 restores the automatic choice.  Returns the previous setting.
  * Host only, thread-safe (one atomic flag). */

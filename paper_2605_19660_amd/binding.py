@@ -30,7 +30,7 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
            "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns",
-           "oscar_debug_force_generic_decode")
+           "oscar_debug_force_generic_decode", "oscar_decode_attn_noalloc")
 
 
 class OscarError(RuntimeError):
@@ -87,6 +87,8 @@ def lib():
     L.oscar_quantize_append.argtypes = [vp, vp, i32, vp, C.POINTER(CCache), i32, u32, vp]
     L.oscar_decode_attn.restype = C.c_int
     L.oscar_decode_attn.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp, sz, vp]
+    L.oscar_decode_attn_noalloc.restype = C.c_int
+    L.oscar_decode_attn_noalloc.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp]
     L.oscar_decode_attn_partial.restype = C.c_int
     L.oscar_decode_attn_partial.argtypes = [vp, C.POINTER(CCache), f32, i32, vp, sz, vp]
     L.oscar_decode_attn_partial_timed.restype = C.c_int
@@ -259,6 +261,19 @@ def decode_attn(cache: Cache, q, out=None, scale: float = 0.0, max_seq_len_hint:
                                  dtype_code(out.dtype), scale, max_seq_len_hint, num_splits,
                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(rc, "oscar_decode_attn")
+    return out
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def decode_attn_noalloc(cache: Cache, q, out, scale: float = 0.0, max_seq_len_hint: int = 0,
+                        num_splits: int = 0, stream=None):
+    """oscar_decode_attn_noalloc: the caller brings `out`; nothing is allocated on either side."""
+    rc = lib().oscar_decode_attn_noalloc(q.data_ptr(), C.byref(cache.c), out.data_ptr(),
+                                         dtype_code(out.dtype), scale, max_seq_len_hint, num_splits,
+                                         _stream_ptr(stream))
+    _check(rc, "oscar_decode_attn_noalloc")
     return out
 
 

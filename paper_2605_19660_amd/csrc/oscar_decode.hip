@@ -539,3 +539,54 @@ extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* 
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
                                   stream);
 }
+
+// ---- the entry point that allocates nothing -------------------------------------------------
+// Split-K partials live in a fixed array inside the library's device image instead of a caller
+// workspace.  In host code the array's name is only a stand-in: its device address is asked of
+// the runtime once per device (each GPU holds its own copy) and kept; kernels get that pointer.
+static __device__ __align__(256) unsigned char scratch[OSCAR_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch_of_current_device(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<void*> ptr_of[kMaxDev];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) {
+    (void)hipGetLastError();
+    return OSCAR_ERR_HIP;
+  }
+  void* p = ptr_of[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return OSCAR_ERR_HIP;
+    }
+    ptr_of[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return OSCAR_OK;
+}
+
+extern "C" int oscar_decode_attn_noalloc(const void* q, const oscar_cache* cache, void* out,
+                                         int32_t out_dtype, float softmax_scale,
+                                         int32_t max_seq_len_hint, int32_t num_splits,
+                                         void* stream) {
+  int rc = check_decode_cache(cache);
+  if (rc != OSCAR_OK) return rc;
+  if (!q || !out || max_seq_len_hint < 0 || num_splits < 0 || num_splits > 512)
+    return OSCAR_ERR_INVALID_ARG;
+  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
+  if (num_splits == 0)
+    num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
+  const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
+  if (need == 0 || need > (size_t)OSCAR_NOALLOC_SCRATCH_BYTES) return OSCAR_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = noalloc_scratch_of_current_device(&ws);
+  if (rc != OSCAR_OK) return rc;
+  // every record of the partials (batch x query head x split) is written by the partial pass
+  // before the reduce pass reads it, so nothing of the previous call's contents has to be cleared
+  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, ws,
+                      (size_t)OSCAR_NOALLOC_SCRATCH_BYTES, stream, nullptr);
+  if (rc != OSCAR_OK) return rc;
+  return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, ws,
+                                  (size_t)OSCAR_NOALLOC_SCRATCH_BYTES, stream);
+}

@@ -22,6 +22,7 @@ SOURCES = {
     "oscar_quantize_allheads.hip": ["-ffp-contract=off"],
     "oscar_decode.hip": [],
     "oscar_decode_mfma.hip": [],
+    "oscar_decode_mfma_zpmin.hip": [],
     "oscar_bf16_decode.hip": [],
     "oscar_probe.hip": [],
 }

@@ -33,6 +33,14 @@
 #include <atomic>
 
 #include "oscar_decode_common.h"
+
+// This file is compiled twice: as it stands for the integer zero-point of Eq. 3-4, and through
+// oscar_decode_mfma_zpmin.hip with OSCAR_MFMA_ZPMIN = 1 for the float zero-point form; the
+// zero-point form is a compile-time constant of the kernel (no branches in the page loop), and
+// the two sets of variants compile side by side.
+#ifndef OSCAR_MFMA_ZPMIN
+#define OSCAR_MFMA_ZPMIN 0
+#endif
 #include "oscar_rowops.h"
 
 namespace {
@@ -146,21 +154,18 @@ template <int HI> __device__ __forceinline__ float mix_scale(float x, uint32_t h
   return r;
 }
 
-// The unpack masks live in scalar registers: an AND with a scalar operand has the short
-// 32-bit encoding, the same AND with a 32-bit literal the long one, and a wave issues short
-// encodings at a higher rate (measured: 4 against 6 cycles per instruction and wave).
+// The unpack masks live in vector registers.  Measured on gfx950 with two or more waves per
+// SIMD: a v_and_b32 or v_lshrrev_b32 whose operands are vector registers (or a literal) issues in
+// about 2.6 clocks per wave, the same instruction with a scalar-register operand in 4.5 -- so the
+// masks are kept out of scalar registers (where the compiler puts such loop constants).
 template <int BITS> struct Masks {
   uint32_t m0, m1, m2;
   __device__ __forceinline__ void init() {
-    if (BITS == 2) {
-      asm volatile("s_mov_b32 %0, 0x00300030" : "=s"(m0));
-      asm volatile("s_mov_b32 %0, 0x00C000C0" : "=s"(m1));
-      asm volatile("s_mov_b32 %0, 0x03000300" : "=s"(m2));
-    } else {
-      asm volatile("s_mov_b32 %0, 0x003C003C" : "=s"(m0));
-      asm volatile("s_mov_b32 %0, 0x03C003C0" : "=s"(m1));
-      m2 = 0;
-    }
+    m0 = BITS == 2 ? 0x00300030u : 0x003C003Cu;
+    m1 = BITS == 2 ? 0x00C000C0u : 0x03C003C0u;
+    m2 = 0x03000300u;
+    asm volatile("" : "+v"(m0), "+v"(m1));
+    if (BITS == 2) asm volatile("" : "+v"(m2));
   }
 };
 
@@ -190,26 +195,31 @@ template <> struct Chunk<4> {
   }
 };
 
-// Page loads go through raw buffer resources (one per pool and page, built on the scalar
-// unit from the wave-uniform page index): the per-lane offset is a loop constant, and a
-// resource of zero length turns the prefetch past a wave's last page into loads that
-// return zeros without touching memory -- the prefetch needs no branch, so the loaded
-// registers are plain loop-carried values (a conditional load made the compiler copy the
-// whole register set, and wait for it, at the end of every iteration).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t page_rsrc(const void* pool, size_t pgi, int bytes,
-                                                            bool valid) {
-  uint8_t* base = const_cast<uint8_t*>(static_cast<const uint8_t*>(pool)) + pgi * (size_t)bytes;
-  return __builtin_amdgcn_make_buffer_rsrc(base, 0, valid ? bytes : 0, 0x00020000);
+// Page loads go through raw buffer resources, one per pool.  The resource's base is fixed for
+// the whole kernel (pool + kv head * page bytes) and spans one page; the page itself is
+// selected by the scalar offset of the load (physical page * kv heads * page bytes), so a new
+// page costs a scalar multiply and add per pool instead of a 64-bit address computation.  The
+// hardware's range check compares the per-lane offset with (number of records - scalar
+// offset), so the record count of a live resource is the end of its page.  The per-lane offset is a loop constant, and a resource of
+// zero length turns the prefetch past a wave's last page into loads that return zeros without
+// touching memory -- the prefetch needs no branch, so the loaded registers are plain
+// loop-carried values (a conditional load made the compiler copy the whole register set, and
+// wait for it, at the end of every iteration).  A single wave issues one instruction about
+// every five clocks whatever its kind, so scalar bookkeeping in the page loop is not free.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t pool_rsrc(const uint8_t* base, uint32_t page_off,
+                                                            int bytes, bool valid) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0,
+                                           valid ? (int)(page_off + (uint32_t)bytes) : 0, 0x00020000);
 }
-__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, int off) {
-  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, int off, uint32_t soff = 0) {
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, (int)soff, 0));
 }
 
 // A lane's two chunks of a tile pair: 16 bytes (2-bit) or 32 bytes (4-bit).
 template <int BITS> struct TilePair;
 template <> struct TilePair<2> {
   uint4 v;
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off) { v = buf_load16(r, off); }
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off, uint32_t so) { v = buf_load16(r, off, so); }
   __device__ __forceinline__ Chunk<2> chunk(int i) const {
     Chunk<2> c;
     c.w[0] = i ? v.z : v.x;
@@ -219,9 +229,9 @@ template <> struct TilePair<2> {
 };
 template <> struct TilePair<4> {
   uint4 v[2];
-  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off) {
-    v[0] = buf_load16(r, off);
-    v[1] = buf_load16(r, off + 16);
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int off, uint32_t so) {
+    v[0] = buf_load16(r, off, so);
+    v[1] = buf_load16(r, off + 16, so);
   }
   __device__ __forceinline__ Chunk<4> chunk(int i) const {
     Chunk<4> c;
@@ -230,15 +240,39 @@ template <> struct TilePair<4> {
   }
 };
 
-// The five buffer resources of one page (wave-uniform, scalar registers).
+// The pools' bases for one kv head and the byte strides between physical pages (wave-uniform).
+struct PoolBases {
+  const uint8_t *kcodes, *kmeta, *knorm, *vcodes, *vmeta;
+  uint32_t s_kcodes, s_kmeta, s_knorm, s_vcodes, s_vmeta;
+  __device__ __forceinline__ void make(const DecodeParams& P, int kvh) {
+    const uint32_t Hkv = (uint32_t)P.c.cfg.n_kv_heads;
+    kcodes = static_cast<const uint8_t*>(P.c.k_codes) + (size_t)kvh * P.g.k_codes_bytes;
+    kmeta = static_cast<const uint8_t*>(P.c.k_meta) + (size_t)kvh * P.g.k_meta_bytes;
+    knorm = static_cast<const uint8_t*>(P.c.k_norms) + (size_t)kvh * P.g.k_norms_bytes;
+    vcodes = static_cast<const uint8_t*>(P.c.v_codes) + (size_t)kvh * P.g.v_codes_bytes;
+    vmeta = static_cast<const uint8_t*>(P.c.v_meta) + (size_t)kvh * P.g.v_meta_bytes;
+    s_kcodes = Hkv * (uint32_t)P.g.k_codes_bytes;
+    s_kmeta = Hkv * (uint32_t)P.g.k_meta_bytes;
+    s_knorm = Hkv * (uint32_t)P.g.k_norms_bytes;
+    s_vcodes = Hkv * (uint32_t)P.g.v_codes_bytes;
+    s_vmeta = Hkv * (uint32_t)P.g.v_meta_bytes;
+  }
+};
+// The five buffer resources of one page and the page's scalar offsets (wave-uniform).
 struct PageRsrc {
   __amdgpu_buffer_rsrc_t kcodes, kmeta, knorm, vcodes, vmeta;
-  __device__ __forceinline__ void make(const DecodeParams& P, size_t pgi, bool valid) {
-    kcodes = page_rsrc(P.c.k_codes, pgi, P.g.k_codes_bytes, valid);
-    kmeta = page_rsrc(P.c.k_meta, pgi, P.g.k_meta_bytes, valid);
-    knorm = page_rsrc(P.c.k_norms, pgi, P.g.k_norms_bytes, valid);
-    vcodes = page_rsrc(P.c.v_codes, pgi, P.g.v_codes_bytes, valid);
-    vmeta = page_rsrc(P.c.v_meta, pgi, P.g.v_meta_bytes, valid);
+  uint32_t o_kcodes, o_kmeta, o_knorm, o_vcodes, o_vmeta;
+  __device__ __forceinline__ void make(const PoolBases& B, const DecodeParams& P, uint32_t phys, bool valid) {
+    o_kcodes = phys * B.s_kcodes;
+    o_kmeta = phys * B.s_kmeta;
+    o_knorm = phys * B.s_knorm;
+    o_vcodes = phys * B.s_vcodes;
+    o_vmeta = phys * B.s_vmeta;
+    kcodes = pool_rsrc(B.kcodes, o_kcodes, P.g.k_codes_bytes, valid);
+    kmeta = pool_rsrc(B.kmeta, o_kmeta, P.g.k_meta_bytes, valid);
+    knorm = pool_rsrc(B.knorm, o_knorm, P.g.k_norms_bytes, valid);
+    vcodes = pool_rsrc(B.vcodes, o_vcodes, P.g.v_codes_bytes, valid);
+    vmeta = pool_rsrc(B.vmeta, o_vmeta, P.g.v_meta_bytes, valid);
   }
 };
 
@@ -251,14 +285,14 @@ template <int BITS, int NGK> struct KeyRegs {
   uint4 kd[NGK], kz[NGK];  // key Delta / zero of positions 8n..8n+7 (operand order)
   uint4 nr;                // norms of tokens 16*T+n, T = 0..7
   __device__ __forceinline__ void load_codes(const PageRsrc& r, int tp, int lane) {
-    kc[tp].load(r.kcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB);
+    kc[tp].load(r.kcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB, r.o_kcodes);
   }
   __device__ __forceinline__ void load_meta(const PageRsrc& r, int g, int lane) {
-    kd[g] = buf_load16(r.kmeta, (g * D + 8 * (lane & 15)) * 2);
-    kz[g] = buf_load16(r.kmeta, ((NGK + g) * D + 8 * (lane & 15)) * 2);
+    kd[g] = buf_load16(r.kmeta, (g * D + 8 * (lane & 15)) * 2, r.o_kmeta);
+    kz[g] = buf_load16(r.kmeta, ((NGK + g) * D + 8 * (lane & 15)) * 2, r.o_kmeta);
   }
   __device__ __forceinline__ void load_norm(const PageRsrc& r, int lane) {
-    nr = buf_load16(r.knorm, 8 * (lane & 15) * 2);
+    nr = buf_load16(r.knorm, 8 * (lane & 15) * 2, r.o_knorm);
   }
   __device__ __forceinline__ void load(const PageRsrc& r, int lane) {
 #pragma unroll
@@ -273,13 +307,13 @@ template <int BITS, int NGV> struct ValRegs {
   TilePair<BITS> vc[4];
   uint4 vd[NGV], vz[NGV];  // value Delta / zero of tokens 16*T+n
   __device__ __forceinline__ void load_codes(const PageRsrc& r, int tp, int lane) {
-    vc[tp].load(r.vcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB);
+    vc[tp].load(r.vcodes, (tp * 64 + (lane & 15) * 4 + (lane >> 4)) * PB, r.o_vcodes);
   }
   __device__ __forceinline__ void load_delta(const PageRsrc& r, int g, int lane) {
-    vd[g] = buf_load16(r.vmeta, (g * R + 8 * (lane & 15)) * 2);
+    vd[g] = buf_load16(r.vmeta, (g * R + 8 * (lane & 15)) * 2, r.o_vmeta);
   }
   __device__ __forceinline__ void load_zero(const PageRsrc& r, int g, int lane) {
-    vz[g] = buf_load16(r.vmeta, ((NGV + g) * R + 8 * (lane & 15)) * 2);
+    vz[g] = buf_load16(r.vmeta, ((NGV + g) * R + 8 * (lane & 15)) * 2, r.o_vmeta);
   }
   __device__ __forceinline__ void load(const PageRsrc& r, int lane) {
 #pragma unroll
@@ -392,7 +426,7 @@ __host__ __device__ constexpr int decode_mfma_wgs_per_cu(int bits, int hp, int n
   return oscar_decode_mfma_wgs_per_cu(bits, hp, ngk, ngv);
 }
 
-template <int BITS, int HP, int NGK, int NGV>
+template <int BITS, int HP, int NGK, int NGV, bool ZPMIN>
 __global__ __launch_bounds__(256, decode_mfma_wgs_per_cu(BITS, HP, NGK, NGV))
 void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   constexpr int TPG = 8 / NGK;  // token tiles per key group
@@ -417,7 +451,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, q4 = lane >> 4;
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
-  const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
+  constexpr bool zp_min = ZPMIN;
 
   // Pages are dealt round-robin: wave w of split s owns pages 4*s + w + 4*S*k.  The page
   // numbers (and so the block-table addresses) do not depend on the sequence length, which
@@ -455,11 +489,13 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   const bool wave_res = 4 * wave < rcount;
 
   // ---- first page and first residual pass: issued before anything is computed ----
+  PoolBases pools;
+  pools.make(P, kvh);
   KeyRegs<BITS, NGK> kr;
   ValRegs<BITS, NGV> vr;
   {
     PageRsrc first;
-    first.make(P, (size_t)__builtin_amdgcn_readlane(tab, 0) * Hkv + kvh, pg_first < n_pages);
+    first.make(pools, P, (uint32_t)__builtin_amdgcn_readlane(tab, 0), pg_first < n_pages);
     kr.load(first, lane);
     vr.load(first, lane);
   }
@@ -642,7 +678,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
                               : __builtin_amdgcn_readlane(tabn, 0);
     PageRsrc nx;   // the wave's next page
-    nx.make(P, (size_t)phys * Hkv + kvh, has_next);
+    nx.make(pools, P, (uint32_t)phys, has_next);
 
     // ---- q K^T ----
     float S[HP][8];
@@ -653,7 +689,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         // per channel, what one unit of Q_h takes off the logit: Delta*z, or -zero when the
         // zero-point is the float group minimum (x = Delta*c + zero)
         float dz[8];
-        if (zp_min) neg_widen8(kr.kz[g], dz);
+        if constexpr (zp_min) neg_widen8(kr.kz[g], dz);
         else mix_mul8(kr.kd[g], kr.kz[g], dz);
         float bias[HP];
 #pragma unroll
@@ -671,11 +707,10 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
           bias[s] = row16_sum(bp);
           uint4 hi, lo;
           mul_split_hi_lo(qs[s], kr.kd[g], hi, lo);
+          // (rows of heads past the group hold zeros either way: their queries are zero)
           const int h = q4 + 4 * s;
-          if (h < gq) {
-            *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
-            *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
-          }
+          *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
+          *reinterpret_cast<uint4*>(&A_tab[row_hi(h) + 1][8 * n]) = lo;
         }
         kr.load_meta(nx, g, lane);
         wave_lds_fence();
@@ -790,7 +825,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
       float dz[8];
-      if (zp_min) neg_widen8(vr.vz[g], dz);
+      if constexpr (zp_min) neg_widen8(vr.vz[g], dz);
       else mix_mul8(vr.vd[g], vr.vz[g], dz);
       vr.load_zero(nx, g, lane);
 #pragma unroll
@@ -801,11 +836,10 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         bv[s][g] += acc_b;
         uint4 hi, lo;
         mul_split_hi_lo(pc[s], vr.vd[g], hi, lo);
+        // (heads past the group produce finite values in rows nobody reads back)
         const int h = q4 + 4 * s;
-        if (h < gq) {
-          *reinterpret_cast<uint4*>(&P_tab[row_hi(h)][8 * n]) = hi;
-          *reinterpret_cast<uint4*>(&P_tab[row_hi(h) + 1][8 * n]) = lo;
-        }
+        *reinterpret_cast<uint4*>(&P_tab[row_hi(h)][8 * n]) = hi;
+        *reinterpret_cast<uint4*>(&P_tab[row_hi(h) + 1][8 * n]) = lo;
       }
       vr.load_delta(nx, g, lane);
       wave_lds_fence();
@@ -911,16 +945,17 @@ template <int BITS, int HP>
 int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipEvent_t e0,
                   hipEvent_t e1) {
   const int ngk = P.g.ngk, ngv = P.g.ngv;
+  constexpr bool ZPM = OSCAR_MFMA_ZPMIN != 0;
   // the event-carrying launch only when a timer asked for it: the plain launch is what a
   // stream capture records
 #define OSCAR_MFMA_CASE(NK, NV)                                                            \
   if (ngk == NK && ngv == NV) {                                                            \
     if (e0 || e1)                                                                          \
-      hipExtLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV>), grid, dim3(256), \
-                            0, st, e0, e1, 0, P, gq);                                      \
+      hipExtLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV, ZPM>), grid,       \
+                            dim3(256), 0, st, e0, e1, 0, P, gq);                           \
     else                                                                                   \
-      hipLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV>), grid, dim3(256), 0, \
-                         st, P, gq);                                                       \
+      hipLaunchKernelGGL((oscar_decode_mfma_kernel<BITS, HP, NK, NV, ZPM>), grid,          \
+                         dim3(256), 0, st, P, gq);                                         \
     return OSCAR_OK;                                                                       \
   }
   OSCAR_MFMA_CASE(1, 4)
@@ -936,10 +971,32 @@ int launch_groups(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipE
   return OSCAR_ERR_UNSUPPORTED;
 }
 
+// every variant of this translation unit's zero-point form
+int launch_this_form(const DecodeParams& P, int gq, dim3 grid, hipStream_t st, hipEvent_t e0,
+                     hipEvent_t e1) {
+  if (P.g.bits == 2)
+    return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st, e0, e1) : launch_groups<2, 2>(P, gq, grid, st, e0, e1);
+  if (P.g.bits == 4)
+    return gq <= 4 ? launch_groups<4, 1>(P, gq, grid, st, e0, e1) : launch_groups<4, 2>(P, gq, grid, st, e0, e1);
+  return OSCAR_ERR_UNSUPPORTED;
+}
+
 }  // namespace
 
+#if OSCAR_MFMA_ZPMIN
+
+int oscar_launch_decode_mfma_zpmin(const void* params, int gq, dim3 grid, hipStream_t st,
+                                   hipEvent_t e0, hipEvent_t e1) {
+  return launch_this_form(*reinterpret_cast<const DecodeParams*>(params), gq, grid, st, e0, e1);
+}
+
+#else
+
+int oscar_launch_decode_mfma_zpmin(const void* params, int gq, dim3 grid, hipStream_t st,
+                                   hipEvent_t e0, hipEvent_t e1);
+
 // Test / profiling switch of oscar_debug_force_generic_decode: the only process-wide state of
-// the library, one relaxed atomic flag read per launch.
+// the library besides the cached device properties, one relaxed atomic flag read per launch.
 static std::atomic<int> g_force_generic{0};
 
 extern "C" int oscar_debug_force_generic_decode(int32_t on) {
@@ -947,8 +1004,8 @@ extern "C" int oscar_debug_force_generic_decode(int32_t on) {
 }
 
 // Launches the matrix-core partial pass when the configuration is one it is built for
-// (fp16 metadata; group sizes 32, 64 or 128 on either side; keys scaled into [-1, 1]); OSCAR_ERR_UNSUPPORTED
-// tells the caller to use the generic kernel.
+// (fp16 metadata; group sizes 32, 64 or 128 on either side; keys scaled into [-1, 1]; page pools
+// below 2 GiB each); OSCAR_ERR_UNSUPPORTED tells the caller to use the generic kernel.
 int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,
                              hipEvent_t e0, hipEvent_t e1) {
   const DecodeParams& P = *reinterpret_cast<const DecodeParams*>(params);
@@ -958,9 +1015,12 @@ int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t 
   if (P.c.cfg.scale_mode != OSCAR_SCALE_L2 && P.c.cfg.scale_mode != OSCAR_SCALE_MAX)
     return OSCAR_ERR_UNSUPPORTED;
   if (g_force_generic.load(std::memory_order_relaxed)) return OSCAR_ERR_UNSUPPORTED;
-  if (P.g.bits == 2)
-    return gq <= 4 ? launch_groups<2, 1>(P, gq, grid, st, e0, e1) : launch_groups<2, 2>(P, gq, grid, st, e0, e1);
-  if (P.g.bits == 4)
-    return gq <= 4 ? launch_groups<4, 1>(P, gq, grid, st, e0, e1) : launch_groups<4, 2>(P, gq, grid, st, e0, e1);
-  return OSCAR_ERR_UNSUPPORTED;
+  // a page is addressed as a 32-bit scalar offset into its pool
+  const unsigned long long units = (unsigned long long)P.c.num_pages * (unsigned long long)P.c.cfg.n_kv_heads;
+  const int biggest = P.g.k_codes_bytes > P.g.v_meta_bytes ? P.g.k_codes_bytes : P.g.v_meta_bytes;
+  if (units * (unsigned long long)biggest > 0x7FFFFFFFull) return OSCAR_ERR_UNSUPPORTED;
+  if (P.c.cfg.zp_mode == OSCAR_ZP_MIN) return oscar_launch_decode_mfma_zpmin(params, gq, grid, st, e0, e1);
+  return launch_this_form(P, gq, grid, st, e0, e1);
 }
+
+#endif

@@ -12,11 +12,17 @@ rotate over several independent cache copies (think: layers) whose total footpri
 twice the 256 MB last-level cache.
 
 Prints ONE JSON line: metric / value / unit / step counts / config, plus
+  parity             a sampled (sequence, kv head) stream of the workload checked against the CPU
+                     oracle before anything is timed (codes bit for bit, decode output in tolerance),
   roofline           the split-K partial kernel: algorithmic bytes per launch over its mean device
-                     time (HIP events attached to the dispatch), against 8 TB/s; `traffic` = HBM
-                     bytes per launch from FETCH_SIZE / WRITE_SIZE counter runs,
+                     time (HIP events attached to every 5th dispatch of the timed region), against
+                     8 TB/s; `traffic` = HBM bytes per launch from FETCH_SIZE / WRITE_SIZE counter runs,
   stream_read_probe  the same timing method on a loads-only kernel of the same launch shape,
-  quantize_append_prefill, bf16_decode (the 16-bit comparator), cpu_baseline (the CPU oracle).
+  quantize_append_prefill, bf16_decode (the 16-bit comparator), cpu_baseline (the CPU oracle),
+  other_workloads    compact records of the other configurations the benchmark description names
+                     (batch 1 x 128K with its 131072-token prefill, batch 64 x 8K at INT2 and INT4
+                     with tokens/s and resident bytes, the GQA-7 omni-like one), each from its own
+                     short run (fixed 20 + 200 steps, whatever --steps says).
 """
 from __future__ import annotations
 
@@ -37,6 +43,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # profiles/); counters cannot be read from inside this process, so the figure is keyed by
 # the workload it was measured on and reported as null for any other.
 MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 181_330_330 + 1_114_214}
+EV_EVERY = 5                # every 5th launch of the decode kernel carries a HIP event pair (5 is
+                            # coprime to the usual copy counts, so every cache copy gets sampled)
 LLC_BYTES = 256 << 20       # Infinity Cache
 
 
@@ -57,6 +65,9 @@ def parse():
                     help="token norm over all kv heads instead of per (token, kv head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="skip the compact records of the other configurations")
+    ap.add_argument("--no-parity", action="store_true", help="skip the in-run check against the oracle")
     ap.add_argument("--bf16-splits", type=int, default=0, help="override the comparator's split-K factor")
     ap.add_argument("--sweep", choices=["context", "batch"], default=None,
                     help="run the context sweep (batch 1) or the batch sweep (4K context) instead "
@@ -132,39 +143,34 @@ def main():
         rows = []
         for (bb, ss) in points:
             wp = base.replace(batch=bb, context=ss, name="%s-b%d-s%d" % (base.name, bb, ss))
-            args.no_cpu_baseline = True
-            r = measure(args, wp, np, torch, ob, synth)
-            rows.append({"batch": bb, "context": ss, "splits": r["config"]["splits"],
-                         "us_per_step": r["value"], "partial_us": r["roofline"]["avg_kernel_us"],
-                         "frac": r["roofline"]["frac"],
-                         "bf16_us": r.get("bf16_decode", {}).get("us_per_step"),
-                         "prefill_us": r["quantize_append_prefill"]["us"],
-                         "cache_mb": r["resident_cache_bytes"] / 1e6})
+            r = compact_record(args, wp, np, torch, ob, synth, bf16=True)
+            r.update({"batch": bb, "context": ss})
+            rows.append(r)
             torch.cuda.empty_cache()
         print(json.dumps({"sweep": args.sweep, "workload": base.name, "bits": base.bits, "points": rows}))
         return
-    print(json.dumps(measure(args, w, np, torch, ob, synth)))
+    res = measure(args, w, np, torch, ob, synth)
+    if not args.no_extra_workloads and args.workload == 1 and not (args.bits or args.k_group or args.v_group
+                                                                    or args.context or args.batch):
+        torch.cuda.empty_cache()
+        extra = []
+        for (wi, bits) in ((2, 2), (3, 2), (3, 4), (4, 2)):
+            extra.append(compact_record(args, synth.CONFIGS[wi].replace(bits=bits), np, torch, ob, synth))
+            torch.cuda.empty_cache()
+        res["other_workloads"] = extra
+    print(json.dumps(res))
 
 
-def measure(args, w, np, torch, ob, synth):
+def make_config(args, w, ob):
     io = {"f32": ob.F32, "bf16": ob.BF16, "f16": ob.F16}[w.io_dtype]
     meta = {"f32": ob.F32, "f16": ob.F16}[w.meta_dtype]
-    cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
-                    w.page_size, io, meta,
-                    norm_scope=ob.NORM_ALL_KV_HEADS if args.norm_all_heads else ob.NORM_PER_HEAD)
-    R = w.page_size
-    total_steps = args.steps + args.warmup
-    pages = (w.context + total_steps) // R + 2
-    stream = torch.cuda.current_stream()
+    return ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group,
+                     w.page_size, io, meta,
+                     norm_scope=ob.NORM_ALL_KV_HEADS if args.norm_all_heads else ob.NORM_PER_HEAD), io
 
-    kd, vd = synth.make_kv_device(w)
-    bytes_tok = synth.cache_bytes_per_token_kvh(w)
-    units = w.batch * w.n_kv_heads * (w.context // R) * R      # packed token-heads read per step
-    cache_bytes = units * bytes_tok
-    # (small caches: at most 32 copies, i.e. those points run warm in the last-level cache)
-    n_copies = args.copies or min(32, max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1))
 
-    # ---- prefill: quantize_append of the whole context, timed per copy ----
+def build_caches(args, w, cfg, kd, vd, pages, n_copies, np, torch, ob, stream):
+    """Timed oscar_quantize_append prefill of the whole context into n_copies caches."""
     caches, t_pre = [], []
     for ci in range(n_copies):
         c = ob.Cache(cfg, w.batch, pages)
@@ -182,63 +188,207 @@ def measure(args, w, np, torch, ob, synth):
         t_pre.append(e0.elapsed_time(e1) * 1e3)
         caches.append(c)
     assert all(int(c.dev_status.item()) == 0 for c in caches)
-    pre_us = float(np.median(t_pre))
-    el = 2 if w.io_dtype != "f32" else 4
-    pre_units = w.batch * w.n_kv_heads * w.context
-    pre_bytes = pre_units * (2 * w.head_dim * el) + units * bytes_tok
+    return caches, float(np.median(t_pre))
 
-    # ---- per-step inputs ----
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(w.seed + 77)
-    dt = ob.torch_dtype(io)
-    new_k = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
-    new_v = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
-    q_host = synth.make_q(w)
-    q = torch.from_numpy(q_host).cuda().to(dt).contiguous()
-    out = torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
-    splits = args.splits or ob.decode_auto_splits(cfg, w.batch, w.context + total_steps)
-    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
 
-    EV_EVERY = 5   # every 5th launch of the decode kernel carries a HIP event pair (5 is
-                   # coprime to the usual copy counts, so every cache copy gets sampled)
+def parity_check(w, cfg, cache, kd, vd, q, q_host, splits, np, torch, ob):
+    """One sampled (sequence, kv head) stream of the workload against the CPU oracle, before any
+    timing: every encoder output of the stream bit for bit, the decode output of its query heads
+    within the stated tolerance (rel-L2 <= 1e-3, max-abs <= 5e-3)."""
+    import oracle
+    b, h = w.batch // 2, (w.n_kv_heads * 5) // 8
+    meta = {"f16": oracle.F16, "f32": oracle.F32}[w.meta_dtype]
+    o = oracle.OracleCache(oracle.OracleConfig(w.head_dim, w.bits, w.k_group, w.v_group, w.page_size, meta),
+                           1, 1, (w.context // w.page_size + 1) * w.page_size)
+    ks = kd[b, :, h].float().cpu().numpy()[None, :, None, :]
+    vs = vd[b, :, h].float().cpu().numpy()[None, :, None, :]
+    o.append(ks, vs, eager=True, nthreads=4)
+    d = ob.debug_dump(cache, b, h)
+    npk, nr = int(o.n_packed[0]), int(o.n_res[0])
+    exact = (int(d["lens"][0]), int(d["lens"][1])) == (npk + nr, nr)
+    for name, got, want in (("k_codes", d["k_codes"][:npk], o.k_codes[0, 0, :npk]),
+                            ("v_codes", d["v_codes"][:npk], o.v_codes[0, 0, :npk]),
+                            ("k_delta", d["k_delta"][:npk // w.k_group], o.k_delta[0, 0, :npk // w.k_group]),
+                            ("k_zero", d["k_zero"][:npk // w.k_group], o.k_zero[0, 0, :npk // w.k_group]),
+                            ("k_norm", d["k_norm"][:npk], o.k_norm[0, 0, :npk]),
+                            ("v_delta", d["v_delta"][:npk], o.v_delta[0, 0, :npk]),
+                            ("v_zero", d["v_zero"][:npk], o.v_zero[0, 0, :npk]),
+                            ("res_k", d["res_k"][:nr], o.res_k[0, 0, :nr])):
+        exact = exact and bool(np.array_equal(got, want))
+    out = ob.decode_attn(cache, q, max_seq_len_hint=w.context, num_splits=splits).cpu().numpy()
+    gq = w.n_q_heads // w.n_kv_heads
+    want = o.decode_attn(q_host[b:b + 1, h * gq:(h + 1) * gq], nthreads=4)[0].astype(np.float64)
+    got = out[b, h * gq:(h + 1) * gq].astype(np.float64)
+    rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
+    mx = float(np.abs(got - want).max())
+    ok = bool(exact and rel <= 1e-3 and mx <= 5e-3)
+    rec = {"checked": True, "passed": ok, "stream": {"sequence": b, "kv_head": h, "tokens": w.context},
+           "encoder_bit_exact": bool(exact), "decode_rel_l2": rel, "decode_max_abs": mx,
+           "tolerance": {"rel_l2": 1e-3, "max_abs": 5e-3}}
+    if not ok:
+        print(json.dumps({"error": "parity check against the oracle failed", "parity": rec}), file=sys.stderr)
+        sys.exit(3)
+    return rec
+
+
+def run_steps(args_steps, warmup, w, cfg, caches, q, new_k, new_v, out, ws, splits, np, torch, ob, stream):
+    """warmup untimed steps, then exactly args_steps timed ones between synchronizations.  A step
+    is one oscar_decode_step call (append one token per sequence + attention).  Every EV_EVERY-th
+    step's partial kernel carries an event pair, whatever the step count."""
+    n_copies = len(caches)
+    hint = w.context + warmup + args_steps + 1
 
     def step(i, ev=None):
-        c = caches[i % n_copies]
-        ob.quantize_append(c, new_k[i], new_v[i], stream=stream)
-        ob.decode_attn_partial(c, q, ws, splits, stream=stream, timer=ev)
-        ob.decode_attn_reduce(c, out, ws, splits, stream=stream)
+        ob.decode_step(caches[i % n_copies], new_k[i], new_v[i], q, out, ws, splits, hint,
+                       stream=stream, timer=ev)
 
     # the first event-carrying launch of a process pays a one-time host cost (tens of ms when
     # the previous process's memory is still being reclaimed): take it in the warm-up
     warm_ev = ob.Timer()
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i, warm_ev if i == 0 else None)
-    if args.warmup == 0:
+    if warmup == 0:
         ob.decode_attn_partial(caches[0], q, ws, splits, stream=stream, timer=warm_ev)
     torch.cuda.synchronize()
     warm_ev.close()
-    evs = [ob.Timer() if i % EV_EVERY == 0 or args.steps < 64 else None for i in range(args.steps)]
+    evs = [ob.Timer() if i % EV_EVERY == 0 else None for i in range(args_steps)]
     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     g0.record(stream)       # events are created at their first record: keep that, and whatever
     g1.record(stream)       # else a first use costs on the host, outside the timed region
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     g0.record(stream)
-    for i in range(args.steps):
-        step(args.warmup + i, evs[i])
+    for i in range(args_steps):
+        step(warmup + i, evs[i])
     g1.record(stream)
     t_enq = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    gpu_span_us = g0.elapsed_time(g1) * 1e3 / args.steps     # device-side span of the same steps
-    enqueue_us = t_enq / args.steps * 1e6                    # host time to enqueue one step
-    us_step = wall / args.steps * 1e6
-    k_us = float(np.mean([e.elapsed_us() for e in evs if e is not None]))
+    k_samples = [e.elapsed_us() for e in evs if e is not None]
     for e in evs:
         if e is not None:
             e.close()
     assert all(int(c.dev_status.item()) == 0 for c in caches)
+    return {"us_step": wall / args_steps * 1e6, "span_us": g0.elapsed_time(g1) * 1e3 / args_steps,
+            "enqueue_us": t_enq / args_steps * 1e6, "k_us": float(np.mean(k_samples)),
+            "k_samples": len(k_samples)}
+
+
+def step_inputs(w, io, total_steps, torch, ob):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 77)
+    dt = ob.torch_dtype(io)
+    new_k = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    new_v = torch.randn(total_steps, w.batch, 1, w.n_kv_heads, w.head_dim, device="cuda", generator=gen).to(dt)
+    return new_k, new_v
+
+
+def compact_record(args, w, np, torch, ob, synth, bf16=False, steps=200, warmup=20):
+    """One configuration in brief: timed whole-context prefill, then `steps` decode steps."""
+    cfg, io = make_config(args, w, ob)
+    R = w.page_size
+    total = steps + warmup
+    pages = (w.context + total) // R + 2
+    stream = torch.cuda.current_stream()
+    kd, vd = synth.make_kv_device(w)
+    bytes_tok = synth.cache_bytes_per_token_kvh(w)
+    units = w.batch * w.n_kv_heads * (w.context // R) * R
+    cache_bytes = units * bytes_tok
+    n_copies = min(32, max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1))
+    caches, pre_us = build_caches(args, w, cfg, kd, vd, pages, n_copies, np, torch, ob, stream)
+    el = 2 if w.io_dtype != "f32" else 4
+    pre_bytes = w.batch * w.n_kv_heads * w.context * (2 * w.head_dim * el) + units * bytes_tok
+    new_k, new_v = step_inputs(w, io, total, torch, ob)
+    q = torch.from_numpy(synth.make_q(w)).cuda().to(ob.torch_dtype(io)).contiguous()
+    out = torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    splits = args.splits or ob.decode_auto_splits(cfg, w.batch, w.context + total)
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    r = run_steps(steps, warmup, w, cfg, caches, q, new_k, new_v, out, ws, splits, np, torch, ob, stream)
+    gbs = cache_bytes / (r["k_us"] * 1e-6) / 1e9
+    rec = {"workload": w.name, "bits": w.bits, "batch": w.batch, "context": w.context,
+           "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "splits": splits,
+           "cache_copies_rotated": n_copies, "steps": steps, "warmup": warmup,
+           "us_per_step": r["us_step"], "device_span_us_per_step": r["span_us"],
+           "partial_us": r["k_us"], "hbm_gbs": gbs, "frac": gbs / HBM_PEAK_GBS,
+           "algorithmic_bytes_per_launch": cache_bytes,
+           "traffic": MEASURED_TRAFFIC.get((w.name, w.bits, splits)),
+           "decode_tokens_per_s": w.batch / (r["us_step"] * 1e-6),
+           "resident_cache_bytes": cache_bytes, "cache_bytes_per_token_kv_head": bytes_tok,
+           "prefill_tokens": w.batch * w.context, "prefill_us": pre_us,
+           "prefill_hbm_gbs": pre_bytes / (pre_us * 1e-6) / 1e9,
+           "prefill_frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    if bf16 and w.io_dtype in ("bf16", "f16"):
+        lens = torch.full((w.batch,), w.context, dtype=torch.int32, device="cuda")
+        kh = kd.permute(0, 2, 1, 3).contiguous()
+        vh = vd.permute(0, 2, 1, 3).contiguous()
+        for _ in range(3):
+            ob.bf16_decode_attn(q, kh, vh, lens, out=out, num_splits=splits, workspace=ws, stream=stream, head_major=True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(20):
+            ob.bf16_decode_attn(q, kh, vh, lens, out=out, num_splits=splits, workspace=ws, stream=stream, head_major=True)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        rec["bf16_us"] = e0.elapsed_time(e1) * 1e3 / 20
+        del kh, vh
+    del caches, kd, vd, new_k, new_v
+    return rec
+
+
+def measure(args, w, np, torch, ob, synth):
+    cfg, io = make_config(args, w, ob)
+    R = w.page_size
+    total_steps = args.steps + args.warmup
+    pages = (w.context + total_steps) // R + 2
+    stream = torch.cuda.current_stream()
+
+    kd, vd = synth.make_kv_device(w)
+    bytes_tok = synth.cache_bytes_per_token_kvh(w)
+    units = w.batch * w.n_kv_heads * (w.context // R) * R      # packed token-heads read per step
+    cache_bytes = units * bytes_tok
+    # (small caches: at most 32 copies, i.e. those points run warm in the last-level cache)
+    n_copies = args.copies or min(32, max(2, math.ceil(2 * LLC_BYTES / cache_bytes) + 1))
+
+    # ---- prefill: quantize_append of the whole context, timed per copy ----
+    caches, pre_us = build_caches(args, w, cfg, kd, vd, pages, n_copies, np, torch, ob, stream)
+    el = 2 if w.io_dtype != "f32" else 4
+    pre_units = w.batch * w.n_kv_heads * w.context
+    pre_bytes = pre_units * (2 * w.head_dim * el) + units * bytes_tok
+
+    # ---- per-step inputs ----
+    dt = ob.torch_dtype(io)
+    new_k, new_v = step_inputs(w, io, total_steps, torch, ob)
+    q_host = synth.make_q(w)
+    q = torch.from_numpy(q_host).cuda().to(dt).contiguous()
+    out = torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
+    splits = args.splits or ob.decode_auto_splits(cfg, w.batch, w.context + total_steps)
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+
+    # ---- parity first, then timing ----
+    parity = None
+    if not args.no_parity and not args.norm_all_heads:
+        parity = parity_check(w, cfg, caches[0], kd, vd, q, q_host, splits, np, torch, ob)
+
+    r = run_steps(args.steps, args.warmup, w, cfg, caches, q, new_k, new_v, out, ws, splits, np, torch, ob, stream)
+    us_step, gpu_span_us, enqueue_us, k_us = r["us_step"], r["span_us"], r["enqueue_us"], r["k_us"]
     achieved = cache_bytes / (k_us * 1e-6) / 1e9
+
+    # the same kernel timed on every launch of a separate, untimed-for-`value` region of decode
+    # steps (cold: the copies keep rotating), for a steadier average than the few samples a short
+    # timed region holds
+    sep = []
+    hint = w.context + total_steps + 1
+    for i in range(48):
+        t = ob.Timer()
+        ob.decode_attn_partial(caches[i % n_copies], q, ws, splits, stream=stream, timer=t)
+        ob.decode_attn_reduce(caches[i % n_copies], out, ws, splits, stream=stream)
+        sep.append(t)
+    torch.cuda.synchronize()
+    sep_us = [t.elapsed_us() for t in sep]
+    for t in sep:
+        t.close()
+    sep_us = float(np.mean(sep_us[8:]))
 
     # the same kernel on ONE cache copy, launched back to back: what it shows when whatever
     # fits of the cache stays in the 256 MB last-level cache (reported beside the cold figure)
@@ -252,7 +402,6 @@ def measure(args, w, np, torch, ob, synth):
         t.close()
     warm_us = float(np.mean(warm))
     prop = torch.cuda.get_device_properties(0)
-
     if args.calibrate_copy:
         src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(src)
@@ -350,7 +499,7 @@ def measure(args, w, np, torch, ob, synth):
                    "bits": w.bits, "k_group": w.k_group, "v_group": w.v_group,
                    "io_dtype": w.io_dtype,
                    "norm_scope": "all kv heads" if args.norm_all_heads else "per kv head",
-        "step": "append 1 token/seq (1 launch) + decode attention (partial + reduce launches)",
+        "step": "oscar_decode_step: append 1 token/seq (1 launch) + decode attention (partial + reduce launches)",
                    "splits": splits, "cache_copies_rotated": n_copies},
         "roofline": {"bound": "hbm",
                      "kernel": ("oscar_decode_mfma_kernel" if w.meta_dtype == "f16"
@@ -375,11 +524,15 @@ def measure(args, w, np, torch, ob, synth):
                    "memory_gib": round(prop.total_memory / 2**30, 1),
                    "l2_cache_mib": round(getattr(prop, "L2_cache_size", 0) / 2**20, 1)},
         "compression_vs_16bit": 2 * w.head_dim * 2 / bytes_tok,
+        "separate_region_kernel_us": sep_us,
+        "kernel_event_samples_in_timed_region": r["k_samples"],
         "quantize_append_prefill": {"tokens": w.batch * w.context, "us": pre_us,
                                     "hbm_gbs": pre_bytes / (pre_us * 1e-6) / 1e9,
                                     "frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                                     "algorithmic_bytes": pre_bytes},
     }
+    if parity:
+        res["parity"] = parity
     if rot:
         res["rotate_keys"] = rot
     if stream_read:

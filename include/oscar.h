@@ -211,6 +211,22 @@ int oscar_decode_attn(const void *q, const oscar_cache *cache, void *out, int32_
                       float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* One decoding step of Algorithm "The OScaR algorithm" (OScaR-Inference, decoding phase) in one
+ * call: oscar_quantize_append of ONE new token per sequence under the decode rule, then
+ * oscar_decode_attn over the updated cache -- the same launches, one trip through the ABI.
+ *   k_new, v_new : device, [batch][1][n_kv_heads][head_dim], io_dtype
+ *   q, out, out_dtype, softmax_scale, num_splits, workspace: as in oscar_decode_attn
+ *   max_seq_len_hint : upper bound on seq_lens[] AFTER this step's append (>= 1)
+ *   partial_timer : NULL, or a timer that receives the duration of the split-K partial kernel
+ *                   of this step (measurement aid, see oscar_timer_create)
+ * Every argument is checked before anything is enqueued; OSCAR_ERR_CAPACITY as in
+ * oscar_quantize_append. */
+typedef struct oscar_timer oscar_timer;
+int oscar_decode_step(const void *k_new, const void *v_new, const void *q, oscar_cache *cache,
+                      void *out, int32_t out_dtype, float softmax_scale, int32_t max_seq_len_hint,
+                      int32_t num_splits, void *workspace, size_t workspace_bytes, void *stream,
+                      oscar_timer *partial_timer);
+
 /* For callers that cannot allocate device memory or carry a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  oscar_decode_attn with the
  * split-K partials kept in a fixed buffer of OSCAR_NOALLOC_SCRATCH_BYTES inside the library's
@@ -286,7 +302,6 @@ int oscar_rotate_columns(const void *w, void *out, int64_t n_rows, int64_t n_col
  * stop marker, with no other kernel in between.  oscar_timer_elapsed_us waits for the kernel; it returns
  * OSCAR_ERR_INVALID_ARG for a timer no launch has used yet.  A timer may be reused by a
  * later launch once its elapsed time has been read.  The caller destroys what it creates. */
-typedef struct oscar_timer oscar_timer;
 int oscar_timer_create(oscar_timer **timer);
 int oscar_timer_destroy(oscar_timer *timer);
 int oscar_timer_elapsed_us(oscar_timer *timer, float *us);

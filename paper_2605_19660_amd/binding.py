@@ -30,7 +30,8 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_bf16_decode_attn", "oscar_debug_dump", "oscar_timer_create",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
            "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns",
-           "oscar_debug_force_generic_decode", "oscar_decode_attn_noalloc")
+           "oscar_debug_force_generic_decode", "oscar_decode_attn_noalloc",
+           "oscar_decode_step")
 
 
 class OscarError(RuntimeError):
@@ -89,6 +90,8 @@ def lib():
     L.oscar_decode_attn.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp, sz, vp]
     L.oscar_decode_attn_noalloc.restype = C.c_int
     L.oscar_decode_attn_noalloc.argtypes = [vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp]
+    L.oscar_decode_step.restype = C.c_int
+    L.oscar_decode_step.argtypes = [vp, vp, vp, C.POINTER(CCache), vp, i32, f32, i32, i32, vp, sz, vp, vp]
     L.oscar_decode_attn_partial.restype = C.c_int
     L.oscar_decode_attn_partial.argtypes = [vp, C.POINTER(CCache), f32, i32, vp, sz, vp]
     L.oscar_decode_attn_partial_timed.restype = C.c_int
@@ -264,6 +267,18 @@ def decode_attn(cache: Cache, q, out=None, scale: float = 0.0, max_seq_len_hint:
     return out
 
 
+def decode_step(cache: Cache, k_new, v_new, q, out, workspace, num_splits: int,
+                max_seq_len_hint: int, scale: float = 0.0, stream=None, timer: "Timer | None" = None):
+    """oscar_decode_step: append one token per sequence (k_new, v_new: [batch, 1, n_kv_heads, d]),
+    then decode attention into `out`; the caller brings workspace and output."""
+    rc = lib().oscar_decode_step(k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(), C.byref(cache.c),
+                                 out.data_ptr(), dtype_code(out.dtype), scale, max_seq_len_hint,
+                                 num_splits, workspace.data_ptr(), workspace.numel(),
+                                 _stream_ptr(stream), timer.handle if timer is not None else None)
+    _check(rc, "oscar_decode_step")
+    return out
+
+
 NOALLOC_SCRATCH_BYTES = 4 << 20
 
 
@@ -273,7 +288,8 @@ def decode_attn_noalloc(cache: Cache, q, out, scale: float = 0.0, max_seq_len_hi
     rc = lib().oscar_decode_attn_noalloc(q.data_ptr(), C.byref(cache.c), out.data_ptr(),
                                          dtype_code(out.dtype), scale, max_seq_len_hint, num_splits,
                                          _stream_ptr(stream))
-    _check(rc, "oscar_decode_attn_noalloc")
+    _check(rc, "oscar_decode_attn_noalloc",
+           "oscar_decode_step")
     return out
 
 

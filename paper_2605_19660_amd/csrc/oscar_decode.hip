@@ -540,6 +540,32 @@ extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* 
                                   stream);
 }
 
+// One decode step as a single call: the new token of every sequence goes through
+// oscar_quantize_append (decode rule), then the attention runs over the updated cache.
+extern "C" int oscar_decode_step(const void* k_new, const void* v_new, const void* q,
+                                 oscar_cache* cache, void* out, int32_t out_dtype,
+                                 float softmax_scale, int32_t max_seq_len_hint, int32_t num_splits,
+                                 void* workspace, size_t workspace_bytes, void* stream,
+                                 oscar_timer* partial_timer) {
+  int rc = check_decode_cache(cache);
+  if (rc != OSCAR_OK) return rc;
+  if (!k_new || !v_new || !q || !out || max_seq_len_hint < 1 || num_splits < 0 || num_splits > 512)
+    return OSCAR_ERR_INVALID_ARG;
+  if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
+  if (num_splits == 0)
+    num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
+  // every argument of the attention is checked before the append is enqueued
+  const size_t need = oscar_decode_workspace_bytes(&cache->cfg, cache->batch, num_splits);
+  if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
+  rc = oscar_quantize_append(k_new, v_new, 1, nullptr, cache, max_seq_len_hint - 1, 0u, stream);
+  if (rc != OSCAR_OK) return rc;
+  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
+                      workspace_bytes, stream, partial_timer);
+  if (rc != OSCAR_OK) return rc;
+  return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
+                                  stream);
+}
+
 // ---- the entry point that allocates nothing -------------------------------------------------
 // Split-K partials live in a fixed array inside the library's device image instead of a caller
 // workspace.  In host code the array's name is only a stand-in: its device address is asked of

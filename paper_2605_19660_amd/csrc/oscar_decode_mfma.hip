@@ -211,8 +211,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t pool_rsrc(const uint8_t* base,
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0,
                                            valid ? (int)(page_off + (uint32_t)bytes) : 0, 0x00020000);
 }
+// Loads are marked non-temporal (streaming): every byte of the cache is read once per launch,
+// and keeping it out of the way of the small kernels around this one took 3 us off a decode
+// step on the 32K-context workload (1 us off this kernel).
 __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, int off, uint32_t soff = 0) {
-  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, (int)soff, 0));
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, off, (int)soff, 2));
 }
 
 // A lane's two chunks of a tile pair: 16 bytes (2-bit) or 32 bytes (4-bit).

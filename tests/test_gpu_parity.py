@@ -738,3 +738,45 @@ def test_full_size_configs_sampled_against_oracle(wi, bits, samples):
         assert_decode_close(out[b, h * gq:(h + 1) * gq], want[0])
     del g, kd, vd
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------- one-call step --
+
+def test_decode_step_equals_append_then_decode_and_the_oracle():
+    """oscar_decode_step = oscar_quantize_append of one token per sequence (decode rule) followed by
+    oscar_decode_attn: identical outputs to the two calls on a twin cache over 140 steps (a
+    deferred flush included), the cache bit-exact against the oracle, errors before any launch."""
+    torch = _torch()
+    ob = _ob()
+    n0, steps, splits = 128 + 120, 140, 3
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=n0 + steps)
+    k, v = synth.make_kv_batch(w)
+    kd, vd = to_dev(k, w.io_dtype), to_dev(v, w.io_dtype)
+    a, o = make_pair(w, 5)
+    b, _ = make_pair(w, 5)
+    for c in (a, b):
+        ob.quantize_append(c, kd[:, :n0].contiguous(), vd[:, :n0].contiguous(), eager=True, max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    ws = torch.empty(ob.decode_workspace_bytes(a.cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    out_a = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    for t in range(steps):
+        q = to_dev(synth.make_q(w, t), w.io_dtype)
+        kt, vt = kd[:, n0 + t:n0 + t + 1].contiguous(), vd[:, n0 + t:n0 + t + 1].contiguous()
+        ob.decode_step(a, kt, vt, q, out_a, ws, splits, n0 + t + 1)
+        ob.quantize_append(b, kt, vt)
+        out_b = ob.decode_attn(b, q, max_seq_len_hint=n0 + t + 1, num_splits=splits)
+        assert torch.equal(out_a, out_b), t
+        o.append(k[:, n0 + t:n0 + t + 1], v[:, n0 + t:n0 + t + 1])
+        if t % 35 == 0 or t == steps - 1:
+            assert_decode_close(out_a.cpu().numpy(), o.decode_attn(synth.make_q(w, t)))
+    assert_cache_equal(a, o, w)
+    # argument errors: nothing is enqueued, the cache does not move
+    before = a.seq_lens.clone()
+    with pytest.raises(ob.OscarError) as e:
+        ob.decode_step(a, kt, vt, q, out_a, torch.empty(8, dtype=torch.uint8, device="cuda"), splits, n0 + steps + 1)
+    assert e.value.status == ob.ERR_WORKSPACE
+    with pytest.raises(ob.OscarError) as e:
+        ob.decode_step(a, kt, vt, q, out_a, ws, splits, 0)
+    assert e.value.status == ob.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.equal(a.seq_lens, before)

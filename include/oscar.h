@@ -159,6 +159,24 @@ const char *oscar_status_string(int status);
 int oscar_cache_sizes(const oscar_config *cfg, int32_t batch, int32_t num_pages,
                       int32_t max_pages_per_seq, oscar_pool_sizes *out);
 
+/* A model keeps one cache per layer (Algorithm "The OScaR algorithm": OScaR-Inference runs in
+ * every layer on that layer's K, V, Q); its L layers share ONE block table (a token's page has
+ * the same number in every layer) and differ in everything else.  Layout of a multi-layer
+ * cache: `all_layers` describes the whole allocation --
+ *   k_codes, k_meta, k_norms, v_codes, v_meta, res_k, res_v, res_norm : [n_layers] slices, each
+ *       of the size oscar_cache_sizes reports for (batch, num_pages, max_pages_per_seq), so a
+ *       pool is indexed [layer][physical page][kv head][bytes]; num_pages = pages PER LAYER
+ *   seq_lens, res_lens : [n_layers][batch]  (a decoding step appends to layer 0 and attends in
+ *       layer 0 before layer 1 has seen the token, so the lengths are per-layer state)
+ *   tickets : [n_layers] (or NULL), dev_status : shared, block_table : shared
+ * oscar_cache_layer fills *layer_cache with the view of one layer (pointer arithmetic on the
+ * host, nothing else); the view is an ordinary oscar_cache for every other call, and views of
+ * different layers may be used on different streams at the same time.
+ * Returns OSCAR_ERR_INVALID_ARG for NULL arguments, n_layers < 1 or layer outside
+ * [0, n_layers), and whatever oscar_cache_sizes returns for the configuration. */
+int oscar_cache_layer(const oscar_cache *all_layers, int32_t n_layers, int32_t layer,
+                      oscar_cache *layer_cache);
+
 /* Number of sequence splits oscar_decode_attn uses when num_splits == 0, for the
  * device current at the time of the call. Host only; >= 1. */
 int32_t oscar_decode_auto_splits(const oscar_config *cfg, int32_t batch, int32_t max_seq_len);
@@ -275,9 +293,14 @@ int oscar_decode_attn_reduce(const oscar_cache *cache, void *out, int32_t out_dt
  *                                    (the paper's fast variant) instead of sqrt and divide;
  *                                    results agree with the exact mode to about one fp16 ulp
  *                                    and are not bit-reproducible on a CPU
+ *   ... | OSCAR_ROTATE_MATRIX_CORE : the rotation as H_8 (x) H_16 with the H_16 factor on matrix
+ *                                    cores (App. "Fused Hadamard-Norm Kernel"); 16-bit io_dtype
+ *                                    only (OSCAR_ERR_UNSUPPORTED for F32).  Same values up to fp32
+ *                                    rounding (another summation order), so not bit-identical
+ *                                    to the cache path; combines with the two flags above
  * Returns OSCAR_ERR_INVALID_ARG for NULL pointers, unknown flags, or FAST_RSQRT without
  * NORMALIZE. */
-enum { OSCAR_ROTATE_NORMALIZE = 1u, OSCAR_ROTATE_FAST_RSQRT = 2u };
+enum { OSCAR_ROTATE_NORMALIZE = 1u, OSCAR_ROTATE_FAST_RSQRT = 2u, OSCAR_ROTATE_MATRIX_CORE = 4u };
 int oscar_rotate(const void *x, void *out, void *norms, int64_t n_vec, int32_t io_dtype,
                  int32_t meta_dtype, uint32_t flags, void *stream);
 

@@ -31,7 +31,7 @@ EXPORTS = ("oscar_version", "oscar_status_string", "oscar_cache_sizes",
            "oscar_timer_destroy", "oscar_timer_elapsed_us", "oscar_decode_attn_partial_timed",
            "oscar_probe_stream_read", "oscar_rotate", "oscar_rotate_columns",
            "oscar_debug_force_generic_decode", "oscar_decode_attn_noalloc",
-           "oscar_decode_step")
+           "oscar_decode_step", "oscar_cache_layer")
 
 
 class OscarError(RuntimeError):
@@ -80,6 +80,8 @@ def lib():
     L.oscar_status_string.argtypes = [C.c_int]
     L.oscar_cache_sizes.restype = C.c_int
     L.oscar_cache_sizes.argtypes = [C.POINTER(CConfig), i32, i32, i32, C.POINTER(CPoolSizes)]
+    L.oscar_cache_layer.restype = C.c_int
+    L.oscar_cache_layer.argtypes = [C.POINTER(CCache), i32, i32, C.POINTER(CCache)]
     L.oscar_decode_auto_splits.restype = i32
     L.oscar_decode_auto_splits.argtypes = [C.POINTER(CConfig), i32, i32]
     L.oscar_decode_workspace_bytes.restype = sz
@@ -224,6 +226,62 @@ class Cache:
         return int(s.k_codes + s.k_meta + s.k_norms + s.v_codes + s.v_meta)
 
 
+class _LayerView:
+    """One layer of a MultiLayerCache: an object with the attributes the call wrappers use."""
+
+    def __init__(self, parent: "MultiLayerCache", layer: int):
+        self.parent, self.layer = parent, layer
+        self.cfg, self.batch, self.max_pages_per_seq = parent.cfg, parent.batch, parent.max_pages_per_seq
+        self._c = CCache()
+        _check(lib().oscar_cache_layer(C.byref(parent._c), parent.n_layers, layer, C.byref(self._c)),
+               "oscar_cache_layer")
+        self.seq_lens, self.res_lens = parent.seq_lens[layer], parent.res_lens[layer]
+        self.dev_status = parent.dev_status
+
+    @property
+    def c(self) -> CCache:
+        return self._c
+
+
+class MultiLayerCache:
+    """n_layers caches that share one block table: every pool is allocated n_layers times as large
+    and sliced per layer by oscar_cache_layer; seq_lens / res_lens are [n_layers, batch]."""
+
+    def __init__(self, cfg: Config, batch: int, max_pages_per_seq: int, n_layers: int, device="cuda",
+                 page_perm=None):
+        import torch
+        self.cfg, self.batch, self.max_pages_per_seq, self.n_layers = cfg, batch, max_pages_per_seq, n_layers
+        self.num_pages = batch * max_pages_per_seq
+        self.device = torch.device(device)
+        sz = cache_sizes(cfg, batch, self.num_pages, max_pages_per_seq)
+        self.sizes = sz
+
+        def pool(nbytes):
+            return torch.zeros(int(nbytes) * n_layers, dtype=torch.uint8, device=self.device)
+
+        self.k_codes, self.k_meta, self.k_norms = pool(sz.k_codes), pool(sz.k_meta), pool(sz.k_norms)
+        self.v_codes, self.v_meta = pool(sz.v_codes), pool(sz.v_meta)
+        self.res_k, self.res_v, self.res_norm = pool(sz.res_k), pool(sz.res_v), pool(sz.res_norm)
+        table = np.arange(batch * max_pages_per_seq, dtype=np.int64)
+        if page_perm is not None:
+            table = np.asarray(page_perm, dtype=np.int64)[:batch * max_pages_per_seq]
+        self.block_table = torch.from_numpy(table.astype(np.int32).reshape(batch, max_pages_per_seq)).to(self.device)
+        self.seq_lens = torch.zeros(n_layers, batch, dtype=torch.int32, device=self.device)
+        self.res_lens = torch.zeros(n_layers, batch, dtype=torch.int32, device=self.device)
+        self.dev_status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.tickets = torch.zeros(n_layers, dtype=torch.int32, device=self.device)
+        self._c = CCache()
+        self._c.cfg = cfg.c()
+        self._c.batch, self._c.max_pages_per_seq, self._c.num_pages = batch, max_pages_per_seq, self.num_pages
+        for n in ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
+                  "block_table", "seq_lens", "res_lens", "dev_status", "tickets"):
+            setattr(self._c, n, getattr(self, n).data_ptr())
+        self.layers = [_LayerView(self, l) for l in range(n_layers)]
+
+    def layer(self, l: int) -> _LayerView:
+        return self.layers[l]
+
+
 def quantize_append(cache: Cache, k, v, new_lens=None, eager: bool = False,
                     max_seq_len_hint: int = -1, stream=None):
     """oscar_quantize_append: k, v device tensors [batch, T, n_kv_heads, d] of the io dtype."""
@@ -288,8 +346,7 @@ def decode_attn_noalloc(cache: Cache, q, out, scale: float = 0.0, max_seq_len_hi
     rc = lib().oscar_decode_attn_noalloc(q.data_ptr(), C.byref(cache.c), out.data_ptr(),
                                          dtype_code(out.dtype), scale, max_seq_len_hint, num_splits,
                                          _stream_ptr(stream))
-    _check(rc, "oscar_decode_attn_noalloc",
-           "oscar_decode_step")
+    _check(rc, "oscar_decode_attn_noalloc")
     return out
 
 
@@ -316,10 +373,11 @@ class Timer:
             self.handle = C.c_void_p()
 
 
-ROTATE_NORMALIZE, ROTATE_FAST_RSQRT = 1, 2
+ROTATE_NORMALIZE, ROTATE_FAST_RSQRT, ROTATE_MATRIX_CORE = 1, 2, 4
 
 
-def rotate(x, normalize: bool = False, fast_rsqrt: bool = False, meta_dtype: int = F16, stream=None):
+def rotate(x, normalize: bool = False, fast_rsqrt: bool = False, meta_dtype: int = F16, stream=None,
+           matrix_core: bool = False):
     """oscar_rotate on a [..., 128] tensor: H(x)/sqrt(128) as fp32, or (normalize) the fp16
     unit-norm rotated vectors and their norms."""
     import torch
@@ -331,7 +389,8 @@ def rotate(x, normalize: bool = False, fast_rsqrt: bool = False, meta_dtype: int
     else:
         out = torch.empty(x.shape, dtype=torch.float32, device=x.device)
         norms = None
-    flags = (ROTATE_NORMALIZE if normalize else 0) | (ROTATE_FAST_RSQRT if fast_rsqrt else 0)
+    flags = ((ROTATE_NORMALIZE if normalize else 0) | (ROTATE_FAST_RSQRT if fast_rsqrt else 0) |
+             (ROTATE_MATRIX_CORE if matrix_core else 0))
     rc = lib().oscar_rotate(x.data_ptr(), out.data_ptr(), None if norms is None else norms.data_ptr(),
                             n_vec, dtype_code(x.dtype), meta_dtype, flags, _stream_ptr(stream))
     _check(rc, "oscar_rotate")

@@ -80,6 +80,33 @@ extern "C" int oscar_cache_sizes(const oscar_config* cfg, int32_t batch, int32_t
   return OSCAR_OK;
 }
 
+extern "C" int oscar_cache_layer(const oscar_cache* all_layers, int32_t n_layers, int32_t layer,
+                                 oscar_cache* layer_cache) {
+  if (!all_layers || !layer_cache || n_layers < 1 || layer < 0 || layer >= n_layers)
+    return OSCAR_ERR_INVALID_ARG;
+  oscar_pool_sizes sz;
+  const int rc = oscar_cache_sizes(&all_layers->cfg, all_layers->batch, all_layers->num_pages,
+                                   all_layers->max_pages_per_seq, &sz);
+  if (rc != OSCAR_OK) return rc;
+  auto slice = [layer](void* base, size_t bytes) -> void* {
+    return base ? static_cast<void*>(static_cast<uint8_t*>(base) + (size_t)layer * bytes) : nullptr;
+  };
+  oscar_cache c = *all_layers;
+  c.k_codes = slice(all_layers->k_codes, sz.k_codes);
+  c.k_meta = slice(all_layers->k_meta, sz.k_meta);
+  c.k_norms = slice(all_layers->k_norms, sz.k_norms);
+  c.v_codes = slice(all_layers->v_codes, sz.v_codes);
+  c.v_meta = slice(all_layers->v_meta, sz.v_meta);
+  c.res_k = slice(all_layers->res_k, sz.res_k);
+  c.res_v = slice(all_layers->res_v, sz.res_v);
+  c.res_norm = slice(all_layers->res_norm, sz.res_norm);
+  c.seq_lens = static_cast<int32_t*>(slice(all_layers->seq_lens, sz.seq_lens));
+  c.res_lens = static_cast<int32_t*>(slice(all_layers->res_lens, sz.res_lens));
+  c.tickets = static_cast<int32_t*>(slice(all_layers->tickets, sz.tickets));
+  *layer_cache = c;   // block_table and dev_status stay shared
+  return OSCAR_OK;
+}
+
 extern "C" size_t oscar_decode_workspace_bytes(const oscar_config* cfg, int32_t batch,
                                                int32_t num_splits) {
   if (!cfg || batch <= 0 || num_splits <= 0 || cfg->n_q_heads <= 0 || cfg->head_dim <= 0) return 0;

@@ -52,6 +52,116 @@ __global__ __launch_bounds__(256) void oscar_rotate_kernel(const IO* __restrict_
   }
 }
 
+// Matrix-core variant of the rotation (App. "Fused Hadamard-Norm Kernel": H_128 = H_8 (x) H_16,
+// the H_16 factor on matrix tiles, the H_8 factor as butterflies).  A vector is read as an
+// 8 x 16 matrix X (x[16 a + b]); H_128 x = vec(H_8 X H_16).  One 16x16x16 MFMA multiplies the
+// 16 rows of two vectors (2 x 8 values of a) by H_16, whose entries (+-1) are exact in the
+// 16-bit operand type, with fp32 accumulation; the accumulator layout leaves the two low bits
+// of a in a lane's four registers (two butterfly stages in registers) and the high bit across
+// lane groups 16 apart (one exchange).  The summation order differs from the butterfly of the
+// cache path, so results agree with it to fp32 rounding, not bit for bit: this variant is an
+// option of oscar_rotate, never of oscar_quantize_append.
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+typedef float float4m __attribute__((ext_vector_type(4)));
+
+template <typename IO> struct MfmaH16;
+template <> struct MfmaH16<__hip_bfloat16> {
+  // +-1 in bf16, element k of this lane's column n: sign = parity(k & n)
+  static __device__ __forceinline__ float4m run(uint2 araw, int n, int kg, float4m c) {
+    short4v a = __builtin_bit_cast(short4v, araw), b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = (short)((__builtin_popcount((4 * kg + i) & n) & 1) ? 0xBF80 : 0x3F80);
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct MfmaH16<__half> {
+  static __device__ __forceinline__ float4m run(uint2 araw, int n, int kg, float4m c) {
+    half4v a = __builtin_bit_cast(half4v, araw), b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = (__builtin_popcount((4 * kg + i) & n) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+  }
+};
+
+// One wave rotates two vectors per step; 4 waves, 8 steps: 64 vectors per workgroup.
+template <typename IO, typename META, bool NORMALIZE>
+__global__ __launch_bounds__(256) void oscar_rotate_mfma_kernel(const IO* __restrict__ x, void* out,
+                                                                META* norms, long long n_vec, int fast) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 15, kg = lane >> 4;      // operand row (vector m/8, a = m%8), k group
+  const long long v_base = ((long long)blockIdx.x * 4 + wave) * 16;
+  for (int step = 0; step < 8; ++step) {
+    const long long v0 = v_base + 2 * step;                 // this step's two vectors
+    if (v0 >= n_vec) break;                                  // wave-uniform
+    // A operand: x[v][16 a + 4 kg .. + 3], 8 bytes per lane; a vector past the end repeats the last
+    const long long va = v0 + (m >> 3) < n_vec ? v0 + (m >> 3) : n_vec - 1;
+    const uint2 araw = *reinterpret_cast<const uint2*>(x + (size_t)va * D + 16 * (m & 7) + 4 * kg);
+    float4m z = MfmaH16<IO>::run(araw, m, kg, (float4m){0.0f, 0.0f, 0.0f, 0.0f});
+    // accumulator: column b = lane % 16, rows 4 kg + i -> vector kg / 2, a = 4 (kg % 2) + i
+    float y0 = z[0] + z[1], y1 = z[0] - z[1], y2 = z[2] + z[3], y3 = z[2] - z[3];   // a bit 0
+    float w[4] = {y0 + y2, y1 + y3, y0 - y2, y1 - y3};                                // a bit 1
+    const bool upper = (kg & 1) != 0;                                                 // a bit 2
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float other = __shfl_xor(w[i], 16, 64);
+      w[i] = upper ? other - w[i] : w[i] + other;
+    }
+    const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] *= c;
+    const long long v = v0 + (kg >> 1);
+    const int b = lane & 15;
+    if (!NORMALIZE) {
+      if (v < n_vec) {
+        float* o = reinterpret_cast<float*>(out) + (size_t)v * D + 16 * (4 * (kg & 1)) + b;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[16 * i] = w[i];
+      }
+      continue;
+    }
+    // token norm: sum of squares over the vector's 128 values = 4 registers x 16 columns x 2 groups
+    float s = (w[0] * w[0] + w[1] * w[1]) + (w[2] * w[2] + w[3] * w[3]);
+#pragma unroll
+    for (int msk = 1; msk <= 16; msk <<= 1) s += __shfl_xor(s, msk, 64);
+    float inv, nf;
+    if (fast) {
+      inv = s > 0.0f ? __builtin_amdgcn_rsqf(s) : 0.0f;
+      nf = round_meta<META>(s * inv);
+    } else {
+      nf = round_meta<META>(sqrtf(s));
+      inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
+    }
+    if (v < n_vec) {
+      __half* o = reinterpret_cast<__half*>(out) + (size_t)v * D + 16 * (4 * (kg & 1)) + b;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[16 * i] = __float2half_rn(pin_f32(w[i] * inv));
+      if (b == 0 && (kg & 1) == 0) norms[v] = from_f32<META>(nf);
+    }
+  }
+}
+
+template <typename IO>
+int launch_rotate_mfma(const void* x, void* out, void* norms, long long n_vec, int meta_dtype,
+                       uint32_t flags, hipStream_t st) {
+  const dim3 grid((unsigned)((n_vec + 63) / 64));
+  const IO* xp = reinterpret_cast<const IO*>(x);
+  const int fast = (flags & OSCAR_ROTATE_FAST_RSQRT) ? 1 : 0;
+  if (!(flags & OSCAR_ROTATE_NORMALIZE)) {
+    hipLaunchKernelGGL((oscar_rotate_mfma_kernel<IO, float, false>), grid, dim3(256), 0, st, xp, out,
+                       (float*)nullptr, n_vec, 0);
+  } else if (meta_dtype == OSCAR_F16) {
+    hipLaunchKernelGGL((oscar_rotate_mfma_kernel<IO, __half, true>), grid, dim3(256), 0, st, xp, out,
+                       reinterpret_cast<__half*>(norms), n_vec, fast);
+  } else if (meta_dtype == OSCAR_F32) {
+    hipLaunchKernelGGL((oscar_rotate_mfma_kernel<IO, float, true>), grid, dim3(256), 0, st, xp, out,
+                       reinterpret_cast<float*>(norms), n_vec, fast);
+  } else {
+    return OSCAR_ERR_UNSUPPORTED;
+  }
+  return OSCAR_OK;
+}
+
 template <typename IO>
 int launch_rotate(const void* x, void* out, void* norms, long long n_vec, int meta_dtype,
                   uint32_t flags, hipStream_t st) {
@@ -134,13 +244,23 @@ extern "C" int oscar_rotate_columns(const void* w, void* out, int64_t n_rows, in
 extern "C" int oscar_rotate(const void* x, void* out, void* norms, int64_t n_vec, int32_t io_dtype,
                             int32_t meta_dtype, uint32_t flags, void* stream) {
   if (!x || !out || n_vec < 0) return OSCAR_ERR_INVALID_ARG;
-  if (flags & ~(uint32_t)(OSCAR_ROTATE_NORMALIZE | OSCAR_ROTATE_FAST_RSQRT)) return OSCAR_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(OSCAR_ROTATE_NORMALIZE | OSCAR_ROTATE_FAST_RSQRT | OSCAR_ROTATE_MATRIX_CORE))
+    return OSCAR_ERR_INVALID_ARG;
   if ((flags & OSCAR_ROTATE_FAST_RSQRT) && !(flags & OSCAR_ROTATE_NORMALIZE)) return OSCAR_ERR_INVALID_ARG;
   if ((flags & OSCAR_ROTATE_NORMALIZE) && !norms) return OSCAR_ERR_INVALID_ARG;
   if (n_vec > ((int64_t)1 << 34)) return OSCAR_ERR_INVALID_ARG;
   if (n_vec == 0) return OSCAR_OK;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   int rc;
+  if (flags & OSCAR_ROTATE_MATRIX_CORE) {
+    // the H_16 factor's entries are exact in the operand type only for 16-bit inputs
+    if (io_dtype == OSCAR_BF16) rc = launch_rotate_mfma<__hip_bfloat16>(x, out, norms, n_vec, meta_dtype, flags, st);
+    else if (io_dtype == OSCAR_F16) rc = launch_rotate_mfma<__half>(x, out, norms, n_vec, meta_dtype, flags, st);
+    else return io_dtype == OSCAR_F32 ? OSCAR_ERR_UNSUPPORTED : OSCAR_ERR_INVALID_ARG;
+    if (rc != OSCAR_OK) return rc;
+    if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
+    return OSCAR_OK;
+  }
   switch (io_dtype) {
     case OSCAR_F32: rc = launch_rotate<float>(x, out, norms, n_vec, meta_dtype, flags, st); break;
     case OSCAR_BF16: rc = launch_rotate<__hip_bfloat16>(x, out, norms, n_vec, meta_dtype, flags, st); break;

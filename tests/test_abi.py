@@ -115,3 +115,35 @@ def test_missing_library_fails_loudly(monkeypatch):
     finally:
         monkeypatch.delenv("OSCAR_HIP_LIB")
         importlib.reload(mod)
+
+
+def test_cache_layer_views_are_plain_pointer_arithmetic():
+    """oscar_cache_layer (host only): layer l of a multi-layer allocation starts l whole per-layer
+    pools into every pool and l * batch entries into the length arrays; block table and status
+    word are shared; bad layer numbers are refused."""
+    cfg = ob.Config(32, 8, bits=4, k_group=32)
+    batch, pages, max_pages, L = 3, 24, 8, 5
+    sz = ob.cache_sizes(cfg, batch, pages, max_pages)
+    allc = ob.CCache()
+    allc.cfg = cfg.c()
+    allc.batch, allc.max_pages_per_seq, allc.num_pages = batch, max_pages, pages
+    names = ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
+             "block_table", "seq_lens", "res_lens", "dev_status", "tickets")
+    base = {n: 0x10000000 * (i + 1) for i, n in enumerate(names)}
+    for n in names:
+        setattr(allc, n, base[n])
+    for layer in range(L):
+        view = ob.CCache()
+        assert ob.lib().oscar_cache_layer(C.byref(allc), L, layer, C.byref(view)) == ob.OK
+        for n in ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
+                  "seq_lens", "res_lens", "tickets"):
+            assert getattr(view, n) == base[n] + layer * getattr(sz, n), (n, layer)
+        assert view.block_table == base["block_table"] and view.dev_status == base["dev_status"]
+        assert (view.batch, view.max_pages_per_seq, view.num_pages) == (batch, max_pages, pages)
+    assert sz.seq_lens == 4 * batch and sz.tickets == 4
+    view = ob.CCache()
+    for bad in (-1, L):
+        assert ob.lib().oscar_cache_layer(C.byref(allc), L, bad, C.byref(view)) == ob.ERR_INVALID_ARG
+    assert ob.lib().oscar_cache_layer(None, L, 0, C.byref(view)) == ob.ERR_INVALID_ARG
+    allc.tickets = None                      # optional pointers stay NULL in the view
+    assert ob.lib().oscar_cache_layer(C.byref(allc), L, 2, C.byref(view)) == ob.OK and not view.tickets

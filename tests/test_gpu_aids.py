@@ -98,6 +98,52 @@ def test_stand_alone_rotation_matches_oracle_transforms(io):
         ob.rotate(xd, normalize=False, fast_rsqrt=True)
 
 
+@pytest.mark.parametrize("io", ["bf16", "f16"])
+def test_matrix_core_rotation_variant_within_tolerance(io):
+    """OSCAR_ROTATE_MATRIX_CORE (App. "Fused Hadamard-Norm Kernel": H_128 = H_8 (x) H_16, the H_16
+    factor on matrix tiles): the same rotation in another summation order, so parity is by
+    tolerance, like the reciprocal-square-root mode: the plain rotation within fp32 rounding of
+    the oracle's (and of the closed-form Hadamard product in double), normalized keys within one
+    fp16 ulp, norms within one ulp of the storage type; fp32 input is refused."""
+    import torch
+    import oracle
+    ob = _ob()
+    rng = np.random.default_rng(4321)
+    n_vec = 64 * 3 + 37                     # ragged: odd count, last workgroup partly empty
+    x = rng.standard_normal((n_vec, 128)).astype(np.float32)
+    x[:, [3, 77]] *= 9.0
+    x *= np.exp(rng.normal(0.0, 0.7, (n_vec, 1))).astype(np.float32)
+    x[5] = 0.0
+    x[n_vec - 1] *= 100.0
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16}[io]
+    xd = torch.from_numpy(x).cuda().to(dt).contiguous()
+    xr = xd.float().cpu().numpy()
+    got = ob.rotate(xd, matrix_core=True).cpu().numpy()
+    want = np.stack([oracle.query_transform(v) for v in xr])
+    i = np.arange(128)
+    H = ((-1.0) ** np.array([[bin(a & b).count("1") for b in i] for a in i])) / np.sqrt(128.0)
+    exact = xr.astype(np.float64) @ H.T
+    scale = np.linalg.norm(xr.astype(np.float64), axis=1, keepdims=True) + 1e-30
+    assert np.abs(got - exact).max() <= 1e-5 * np.abs(exact).max()
+    assert (np.abs(got - exact) / scale).max() <= 4e-7          # fp32 accumulation of 128 exact terms
+    assert (np.abs(got - want) / scale).max() <= 6e-7
+    assert not got[5].any()
+    for meta, ometa, ulp in ((ob.F16, oracle.F16, 2.0 ** -10), (ob.F32, oracle.F32, 2.0 ** -22)):
+        for fast in (False, True):
+            u, n = ob.rotate(xd, normalize=True, meta_dtype=meta, matrix_core=True, fast_rsqrt=fast)
+            u, n = u.float().cpu().numpy(), n.float().cpu().numpy()
+            ref = [oracle.key_transform(v, meta_dtype=ometa) for v in xr]
+            u_ref = np.stack([r[0] for r in ref])
+            n_ref = np.asarray([r[1] for r in ref], np.float32)
+            assert np.all(np.abs(n - n_ref) <= ulp * n_ref), (meta, fast)
+            # one fp16 ulp of the element, plus what the norm's own ulp moves it
+            assert np.all(np.abs(u - u_ref) <= (2.0 ** -10 + 2 * ulp) * np.abs(u_ref) + 2.0 ** -24), (meta, fast)
+            assert n[5] == 0.0 and not u[5].any()
+    with pytest.raises(ob.OscarError) as e:
+        ob.rotate(xd.float(), matrix_core=True)
+    assert e.value.status == ob.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_weight_preprocessing_rotations(dt):
     """OScaR-Preprocess (Algorithm "The OScaR algorithm"): W_V <- W_V H and W_O <- H W_O, one H per

@@ -780,3 +780,53 @@ def test_decode_step_equals_append_then_decode_and_the_oracle():
     assert e.value.status == ob.ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert torch.equal(a.seq_lens, before)
+
+
+# --------------------------------------------------------------- multi-layer --
+
+def test_three_layers_share_one_block_table():
+    """A three-layer cache (pools [layer][page][kv head], per-layer lengths, ONE shuffled block
+    table): every layer takes its own K, V (prefill, then decode steps in layer order: append and
+    attend in layer 0 before layer 1 sees the token, with a flush on the way), and is compared
+    with its own oracle cache: encoder outputs bit for bit, attention in tolerance.  Layers must
+    not see each other's data although they share page numbers."""
+    torch = _torch()
+    ob = _ob()
+    L, n0, steps = 3, 128 * 2 + 100, 40
+    w = synth.LLAMA8B_32K.replace(batch=2, n_q_heads=8, n_kv_heads=2, context=n0 + steps)
+    rng = np.random.default_rng(17)
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads)
+    ml = ob.MultiLayerCache(cfg, w.batch, 5, L, page_perm=rng.permutation(w.batch * 5))
+    ks, vs, oracles = [], [], []
+    for l in range(L):
+        wl = w.replace(config_id=40 + l)               # different seed per layer
+        k, v = synth.make_kv_batch(wl)
+        ks.append(k)
+        vs.append(v)
+        oracles.append(OracleCache(OracleConfig(), w.batch, w.n_kv_heads, 6 * 128))
+    for l in range(L):
+        ob.quantize_append(ml.layer(l), to_dev(ks[l][:, :n0], w.io_dtype), to_dev(vs[l][:, :n0], w.io_dtype),
+                           eager=True, max_seq_len_hint=0)
+        oracles[l].append(ks[l][:, :n0], vs[l][:, :n0], eager=True)
+    splits = 2
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    for t in range(steps):
+        for l in range(L):
+            q = synth.make_q(w, 100 * l + t)
+            ob.decode_step(ml.layer(l), to_dev(ks[l][:, n0 + t:n0 + t + 1], w.io_dtype),
+                           to_dev(vs[l][:, n0 + t:n0 + t + 1], w.io_dtype), to_dev(q, w.io_dtype),
+                           out, ws, splits, n0 + t + 1)
+            oracles[l].append(ks[l][:, n0 + t:n0 + t + 1], vs[l][:, n0 + t:n0 + t + 1])
+            if t % 13 == 0 or t == steps - 1:
+                assert_decode_close(out.cpu().numpy(), oracles[l].decode_attn(q))
+        # between layers of a step the lengths differ by one token
+        assert ml.seq_lens[:, 0].tolist() == [n0 + t + 1] * L
+    for l in range(L):
+        assert_cache_equal(ml.layer(l), oracles[l], w)
+    assert int(ml.dev_status.item()) == 0 and int(ml.tickets.abs().sum().item()) == 0
+    # the helper rejects what it cannot slice
+    import ctypes as C
+    view = ob.CCache()
+    assert ob.lib().oscar_cache_layer(C.byref(ml._c), L, L, C.byref(view)) == ob.ERR_INVALID_ARG
+    assert ob.lib().oscar_cache_layer(C.byref(ml._c), 0, 0, C.byref(view)) == ob.ERR_INVALID_ARG

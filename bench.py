@@ -42,7 +42,9 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # each scaled by the same counter's reading for a plain 256 MiB copy kernel (summary under
 # profiles/); counters cannot be read from inside this process, so the figure is keyed by
 # the workload it was measured on and reported as null for any other.
-MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 181_330_330 + 1_114_214}
+MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 182_491_434,
+                    ("long-b1-s128k", 2, 64): 91_636_853,
+                    ("omni-b4-g7-s64k", 2, 32): 92_733_549}
 EV_EVERY = 5                # every 5th launch of the decode kernel carries a HIP event pair (5 is
                             # coprime to the usual copy counts, so every cache copy gets sampled)
 LLC_BYTES = 256 << 20       # Infinity Cache

@@ -473,22 +473,28 @@ def measure(args, w, np, torch, ob, synth):
     # ---- stand-alone rotation + token scaling of all keys (kernel (i) on its own) ----
     rot = None
     if w.meta_dtype == "f16":
-        ts = []
-        for i in range(4):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            ku, kn = ob.rotate(kd, normalize=True, stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            if i:
-                ts.append(e0.elapsed_time(e1) * 1e3)
-            del ku, kn
-        r_us = float(np.median(ts))
+        def time_rotate(matrix_core):
+            ts = []
+            for i in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                ku, kn = ob.rotate(kd, normalize=True, stream=stream, matrix_core=matrix_core)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                if i:
+                    ts.append(e0.elapsed_time(e1) * 1e3)
+                del ku, kn
+            return float(np.median(ts))
+        r_us = time_rotate(False)
         r_bytes = pre_units * (w.head_dim * el + w.head_dim * 2 + 2)
         rot = {"vectors": pre_units, "us": r_us, "hbm_gbs": r_bytes / (r_us * 1e-6) / 1e9,
                "frac": r_bytes / (r_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": r_bytes,
                "what": "oscar_rotate(NORMALIZE) on every key vector: read input, write fp16 K_u + norm "
                        "(includes the output allocation of the binding)"}
+        if w.io_dtype in ("bf16", "f16"):
+            m_us = time_rotate(True)
+            rot["matrix_core_us"] = m_us
+            rot["matrix_core_frac"] = r_bytes / (m_us * 1e-6) / 1e9 / HBM_PEAK_GBS
 
     res = {
         "metric": "int%d_decode_attn_us_per_step" % w.bits,

@@ -54,33 +54,35 @@ __global__ __launch_bounds__(256) void oscar_rotate_kernel(const IO* __restrict_
 
 // Matrix-core variant of the rotation (App. "Fused Hadamard-Norm Kernel": H_128 = H_8 (x) H_16,
 // the H_16 factor on matrix tiles, the H_8 factor as butterflies).  A vector is read as an
-// 8 x 16 matrix X (x[16 a + b]); H_128 x = vec(H_8 X H_16).  One 16x16x16 MFMA multiplies the
-// 16 rows of two vectors (2 x 8 values of a) by H_16, whose entries (+-1) are exact in the
-// 16-bit operand type, with fp32 accumulation; the accumulator layout leaves the two low bits
-// of a in a lane's four registers (two butterfly stages in registers) and the high bit across
-// lane groups 16 apart (one exchange).  The summation order differs from the butterfly of the
-// cache path, so results agree with it to fp32 rounding, not bit for bit: this variant is an
-// option of oscar_rotate, never of oscar_quantize_append.
+// 8 x 16 matrix X (x[16 a + b]); H_128 x = vec(H_8 X H_16).  One 16x16x16 MFMA computes
+// H_16 X^T for two vectors at once: operand A is H_16 (entries +-1, exact in the 16-bit operand
+// type), operand B holds the 16 columns (vector, a) with the 16 values of b along the
+// contraction; accumulation is fp32.  The accumulator leaves a lane with four consecutive b of
+// one (vector, a) -- its output is one 8- or 16-byte store -- and the H_8 factor is three
+// butterfly stages across the lanes of a, labelled as everywhere else so that each partner is
+// one DPP control.  The summation order differs from the butterfly of the cache path, so
+// results agree with it to fp32 rounding, not bit for bit: this variant is an option of
+// oscar_rotate, never of oscar_quantize_append.
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef _Float16 half4v __attribute__((ext_vector_type(4)));
 typedef float float4m __attribute__((ext_vector_type(4)));
 
 template <typename IO> struct MfmaH16;
 template <> struct MfmaH16<__hip_bfloat16> {
-  // +-1 in bf16, element k of this lane's column n: sign = parity(k & n)
-  static __device__ __forceinline__ float4m run(uint2 araw, int n, int kg, float4m c) {
-    short4v a = __builtin_bit_cast(short4v, araw), b;
+  // A = H_16[m][4 kg .. 4 kg + 3] as bf16 (+-1), B = the lane's four inputs as they are
+  static __device__ __forceinline__ float4m run(uint2 xraw, int m, int kg) {
+    short4v h, xb = __builtin_bit_cast(short4v, xraw);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) b[i] = (short)((__builtin_popcount((4 * kg + i) & n) & 1) ? 0xBF80 : 0x3F80);
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) h[i] = (short)((__builtin_popcount((4 * kg + i) & m) & 1) ? 0xBF80 : 0x3F80);
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(h, xb, (float4m){0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
   }
 };
 template <> struct MfmaH16<__half> {
-  static __device__ __forceinline__ float4m run(uint2 araw, int n, int kg, float4m c) {
-    half4v a = __builtin_bit_cast(half4v, araw), b;
+  static __device__ __forceinline__ float4m run(uint2 xraw, int m, int kg) {
+    half4v h, xb = __builtin_bit_cast(half4v, xraw);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) b[i] = (__builtin_popcount((4 * kg + i) & n) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
-    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) h[i] = (__builtin_popcount((4 * kg + i) & m) & 1) ? (_Float16)-1.0f : (_Float16)1.0f;
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(h, xb, (float4m){0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0);
   }
 };
 
@@ -89,41 +91,46 @@ template <typename IO, typename META, bool NORMALIZE>
 __global__ __launch_bounds__(256) void oscar_rotate_mfma_kernel(const IO* __restrict__ x, void* out,
                                                                 META* norms, long long n_vec, int fast) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int m = lane & 15, kg = lane >> 4;      // operand row (vector m/8, a = m%8), k group
+  const int n = lane & 15, kg = lane >> 4;
+  // column n of the tile = (vector, a): the row-lane labelling of the butterflies
+  const int col = channel_group_of_row_lane(n);
+  const int a = col & 7, vl = col >> 3;
+  uint32_t sgn[3];
+#pragma unroll
+  for (int st = 0; st < 3; ++st) sgn[st] = ((a >> st) & 1) ? 0x80000000u : 0u;
   const long long v_base = ((long long)blockIdx.x * 4 + wave) * 16;
   for (int step = 0; step < 8; ++step) {
     const long long v0 = v_base + 2 * step;                 // this step's two vectors
     if (v0 >= n_vec) break;                                  // wave-uniform
-    // A operand: x[v][16 a + 4 kg .. + 3], 8 bytes per lane; a vector past the end repeats the last
-    const long long va = v0 + (m >> 3) < n_vec ? v0 + (m >> 3) : n_vec - 1;
-    const uint2 araw = *reinterpret_cast<const uint2*>(x + (size_t)va * D + 16 * (m & 7) + 4 * kg);
-    float4m z = MfmaH16<IO>::run(araw, m, kg, (float4m){0.0f, 0.0f, 0.0f, 0.0f});
-    // accumulator: column b = lane % 16, rows 4 kg + i -> vector kg / 2, a = 4 (kg % 2) + i
-    float y0 = z[0] + z[1], y1 = z[0] - z[1], y2 = z[2] + z[3], y3 = z[2] - z[3];   // a bit 0
-    float w[4] = {y0 + y2, y1 + y3, y0 - y2, y1 - y3};                                // a bit 1
-    const bool upper = (kg & 1) != 0;                                                 // a bit 2
+    const long long v = v0 + vl;
+    const long long vc = v < n_vec ? v : n_vec - 1;          // a vector past the end repeats the last
+    // operand B: x[v][16 a + 4 kg .. + 3], 8 bytes per lane
+    const uint2 xraw = *reinterpret_cast<const uint2*>(x + (size_t)vc * D + 16 * a + 4 * kg);
+    // accumulator: rows 4 kg + i = b, column n: w[i] = (X H_16)[a][4 kg + i] of vector vl
+    float4m z = MfmaH16<IO>::run(xraw, n, kg);
+    float w[4] = {z[0], z[1], z[2], z[3]};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float other = __shfl_xor(w[i], 16, 64);
-      w[i] = upper ? other - w[i] : w[i] + other;
-    }
+    for (int i = 0; i < 4; ++i) w[i] = partner<0>(w[i]) + __uint_as_float(__float_as_uint(w[i]) ^ sgn[0]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = partner<1>(w[i]) + __uint_as_float(__float_as_uint(w[i]) ^ sgn[1]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = partner<2>(w[i]) + __uint_as_float(__float_as_uint(w[i]) ^ sgn[2]);
     const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[i] *= c;
-    const long long v = v0 + (kg >> 1);
-    const int b = lane & 15;
+    const size_t o_idx = (size_t)v * D + 16 * a + 4 * kg;
     if (!NORMALIZE) {
-      if (v < n_vec) {
-        float* o = reinterpret_cast<float*>(out) + (size_t)v * D + 16 * (4 * (kg & 1)) + b;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) o[16 * i] = w[i];
-      }
+      if (v < n_vec)
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o_idx) = make_float4(w[0], w[1], w[2], w[3]);
       continue;
     }
-    // token norm: sum of squares over the vector's 128 values = 4 registers x 16 columns x 2 groups
+    // token norm: sum of squares over the vector's 128 values = 4 registers x 8 lanes of a x 4 groups
     float s = (w[0] * w[0] + w[1] * w[1]) + (w[2] * w[2] + w[3] * w[3]);
-#pragma unroll
-    for (int msk = 1; msk <= 16; msk <<= 1) s += __shfl_xor(s, msk, 64);
+    s += partner<0>(s);
+    s += partner<1>(s);
+    s += partner<2>(s);
+    s += __shfl_xor(s, 16, 64);
+    s += __shfl_xor(s, 32, 64);
     float inv, nf;
     if (fast) {
       inv = s > 0.0f ? __builtin_amdgcn_rsqf(s) : 0.0f;
@@ -133,10 +140,11 @@ __global__ __launch_bounds__(256) void oscar_rotate_mfma_kernel(const IO* __rest
       inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
     }
     if (v < n_vec) {
-      __half* o = reinterpret_cast<__half*>(out) + (size_t)v * D + 16 * (4 * (kg & 1)) + b;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) o[16 * i] = __float2half_rn(pin_f32(w[i] * inv));
-      if (b == 0 && (kg & 1) == 0) norms[v] = from_f32<META>(nf);
+      uint2 pk;
+      pk.x = half_bits(pin_f32(w[0] * inv)) | (half_bits(pin_f32(w[1] * inv)) << 16);
+      pk.y = half_bits(pin_f32(w[2] * inv)) | (half_bits(pin_f32(w[3] * inv)) << 16);
+      *reinterpret_cast<uint2*>(reinterpret_cast<__half*>(out) + o_idx) = pk;
+      if (a == 0 && kg == 0) norms[v] = from_f32<META>(nf);
     }
   }
 }

@@ -43,6 +43,16 @@
 #endif
 #include "oscar_rowops.h"
 
+// A prefetch that refills registers in place must not be moved, by the instruction scheduler,
+// above the last read of the registers' old contents: the arriving data then lands in other
+// registers and is copied home, and the copy waits for a load that was only just issued.
+// The fence keeps vector-ALU and vector-memory instructions on their side of it; scalar,
+// matrix and LDS instructions may still cross.
+#ifndef OSCAR_PREFETCH_FENCE_MASK
+#define OSCAR_PREFETCH_FENCE_MASK 0x38C
+#endif
+#define OSCAR_PREFETCH_FENCE() __builtin_amdgcn_sched_barrier(OSCAR_PREFETCH_FENCE_MASK)
+
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -731,6 +741,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
             u32x4 b0[4], b1[4];
             kr.kc[T >> 1].chunk(0).operands(b0, masks);
             kr.kc[T >> 1].chunk(1).operands(b1, masks);
+            OSCAR_PREFETCH_FENCE();
             kr.load_codes(nx, T >> 1, lane);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
@@ -750,6 +761,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
                   areg[kk], __builtin_bit_cast(half8, b0[kk]), acc0, 0, 0, 0);
             asm volatile("" ::: "memory");
             kr.kc[T >> 1].chunk(1).operands(b0, masks);
+            OSCAR_PREFETCH_FENCE();
             kr.load_codes(nx, T >> 1, lane);
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
@@ -830,7 +842,6 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
       float dz[8];
       if constexpr (zp_min) neg_widen8(vr.vz[g], dz);
       else mix_mul8(vr.vd[g], vr.vz[g], dz);
-      vr.load_zero(nx, g, lane);
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
         float acc_b = 0.0f;
@@ -858,6 +869,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
           u32x4 b0[4], b1[4];
           vr.vc[ct >> 1].chunk(0).operands(b0, masks);
           vr.vc[ct >> 1].chunk(1).operands(b1, masks);
+          OSCAR_PREFETCH_FENCE();
           vr.load_codes(nx, ct >> 1, lane);
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) {
@@ -875,6 +887,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
                 preg[kk], __builtin_bit_cast(half8, b0[kk]), O[ct], 0, 0, 0);
           asm volatile("" ::: "memory");
           vr.vc[ct >> 1].chunk(1).operands(b0, masks);
+          OSCAR_PREFETCH_FENCE();
           vr.load_codes(nx, ct >> 1, lane);
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk)
@@ -883,6 +896,12 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         }
       }
     }
+    // The zero-points of the next page are fetched last, when every temporary of the
+    // iteration is dead: fetched where they are consumed (inside the value groups), the
+    // compiler parked the arriving registers elsewhere and moved half of each to its home
+    // straight away, which made the wave wait for loads it had just issued.
+#pragma unroll
+    for (int g = 0; g < NGV; ++g) vr.load_zero(nx, g, lane);
   }
   }
 

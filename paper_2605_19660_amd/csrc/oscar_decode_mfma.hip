@@ -53,6 +53,10 @@
 #endif
 #define OSCAR_PREFETCH_FENCE() __builtin_amdgcn_sched_barrier(OSCAR_PREFETCH_FENCE_MASK)
 
+#ifndef OSCAR_DECODE_PRIORITY
+#define OSCAR_DECODE_PRIORITY 1
+#endif
+
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -675,6 +679,17 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   _Float16(*A_tab)[TABW] = s_A[wave];
   _Float16(*P_tab)[TABW] = s_P[wave];
 
+  // Issue priority follows what is left to do.  Two workgroups share a CU, so every SIMD holds
+  // one wave of each; between waves of equal priority the older one wins every issue slot it
+  // can use, and the younger workgroup ran at 40 % of the older one's pace until that one was
+  // done, then finished alone, without a partner to hide its stalls behind.  A wave therefore
+  // lowers its priority as it gets through its pages (quarter by quarter): whichever wave of a
+  // SIMD is behind is served first, and the two finish together.
+  const int n_iter = pg_first < n_pages ? (n_pages - pg_first + pstride - 1) / pstride : 0;
+  const int prio_step = max(1, (n_iter + 3) >> 2);
+  int prio_next = prio_step, prio_level = 0;
+  if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(3);
+
   // Iterations come in chunks of 64 so that the table register is only reloaded between
   // chunks; tabn (lane 0) is the first entry of the following chunk.
   for (int it0 = 0; pg_first + pstride * it0 < n_pages; it0 += 64) {
@@ -686,6 +701,13 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   asm volatile("" ::"v"(tab), "v"(tabn));
   for (int iti = 0; iti < it_end; ++iti) {
     const int pg = pg_first + pstride * (it0 + iti);
+    if (OSCAR_DECODE_PRIORITY && it0 + iti == prio_next) {
+      prio_next += prio_step;
+      ++prio_level;
+      if (prio_level == 1) __builtin_amdgcn_s_setprio(2);
+      else if (prio_level == 2) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+    }
     const bool has_next = pg + pstride < n_pages;
     // entries past the wave's last page read as 0 (a valid page index) and the load is void
     const int phys = iti < 63 ? __builtin_amdgcn_readlane(tab, iti + 1)
@@ -905,6 +927,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   }
   }
 
+  if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(0);
   // ---- wave results -> LDS ----
   {
     const float unscale = ldexpf(1.0f, 24 - xv_cur - slot_bitpos_min(BITS));
@@ -929,18 +952,25 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 
   // ---- merge the 4 wave states and the residual state, write the split's record ----
   __syncthreads();
-  const int ch = tid >> 1, th = tid & 1;   // (channel, head parity)
+  // a thread owns one channel of every second head (the head parity is wave-uniform, so no
+  // lane idles); the reads of a head are independent and go out together
+  const int ch = tid & (D - 1), hh = __builtin_amdgcn_readfirstlane(tid >> 7);
 #pragma unroll
-  for (int h = 0; h < OSCAR_MAX_GQA; ++h) {
-    if (h < gq && (h & 1) == th) {
-      float M = -INFINITY;
+  for (int k = 0; k < OSCAR_MAX_GQA / 2; ++k) {
+    const int h = hh + 2 * k;
+    if (h < gq) {
+      float m[4], o[4];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) M = fmaxf(M, s_wm[w][h]);
+      for (int w = 0; w < 4; ++w) {
+        m[w] = s_wm[w][h];
+        o[w] = s_o[w][h][ch];
+      }
+      const float M = fmaxf(fmaxf(m[0], m[1]), fmaxf(m[2], m[3]));
       float acc = 0.0f;
       if (M != -INFINITY) {
 #pragma unroll
         for (int w = 0; w < 4; ++w)
-          if (s_wm[w][h] != -INFINITY) acc += s_o[w][h][ch] * __builtin_amdgcn_exp2f(s_wm[w][h] - M);
+          if (m[w] != -INFINITY) acc += o[w] * __builtin_amdgcn_exp2f(m[w] - M);
       }
       const size_t rec = ((size_t)b * Hq + (size_t)kvh * gq + h) * P.num_splits + split;
       P.ws[rec * WS_STRIDE + ch] = acc;

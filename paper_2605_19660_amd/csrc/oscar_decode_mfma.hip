@@ -505,7 +505,20 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   const int rcount = min(r, t_lo + rs) - t_lo;
   const bool wave_res = 4 * wave < rcount;
 
-  // ---- first page and first residual pass: issued before anything is computed ----
+  // ---- first residual pass and first page: issued before anything is computed.  The residual
+  // tokens go first: they need no block-table entry, they are few, and the plain-ALU attention
+  // over them then runs while the page is still on its way.  Waves without residual tokens skip
+  // their loads (a void load still takes its turn in the CU's address unit, and at kernel start
+  // all eight waves of a CU queue there). ----
+  ResRsrc rres;
+  rres.make(P, ((size_t)b * Hkv + kvh) * R, wave_res);
+  // slot of the wave's token i of pass p0, clamped to the slice (masked where it is used)
+  auto res_slot = [&](int p0, int i) { return t_lo + max(0, min(p0 + 4 * wave + i, rcount - 1)); };
+  ResTok rt_first[4];   // the wave's four tokens of the first residual pass
+  if (wave_res) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rt_first[i].load(rres, res_slot(0, i), cg);
+  }
   PoolBases pools;
   pools.make(P, kvh);
   KeyRegs<BITS, NGK> kr;
@@ -516,13 +529,6 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     kr.load(first, lane);
     vr.load(first, lane);
   }
-  ResRsrc rres;
-  rres.make(P, ((size_t)b * Hkv + kvh) * R, wave_res);
-  // slot of the wave's token i of pass p0, clamped to the slice (masked where it is used)
-  auto res_slot = [&](int p0, int i) { return t_lo + max(0, min(p0 + 4 * wave + i, rcount - 1)); };
-  ResTok rt_first[4];   // the wave's four tokens of the first residual pass
-#pragma unroll
-  for (int i = 0; i < 4; ++i) rt_first[i].load(rres, res_slot(0, i), cg);
 
   // this wave's operand tables start as zeros (rows of absent heads stay zero)
   for (int i = lane; i < 16 * TABW / 8; i += 64) {
@@ -570,6 +576,10 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) ow[s][c] = 0.0f;
     }
+    // (the raw norms stay opaque until here: converted where they were loaded, they made the
+    // wave wait for the loads, and for the whole first page behind them, before the query rotation)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(rt_first[i].nrm));
     for (int p0 = 0; p0 + 4 * wave < rcount; p0 += 16) {
       float sc[HP][4], vv[4][8];
 #pragma unroll

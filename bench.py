@@ -233,6 +233,28 @@ def parity_check(w, cfg, cache, kd, vd, q, q_host, splits, np, torch, ob):
     return rec
 
 
+PREHEAT_S = 0.15
+
+
+def preheat(caches, q, out, ws, splits, torch, ob, stream, seconds=PREHEAT_S):
+    """Keeps the GPU busy with decode-attention launches (no appends: these are not steps) for
+    `seconds` right before the warm-up steps.  After the host-side work that precedes the timed
+    region (building inputs, the oracle check) the GPU has been idle for seconds and its clocks
+    take tens of milliseconds of continuous work to come back up: measured here, the same kernel
+    ran 15-30 % slower during the first ~30 ms after such a pause.  A decode loop in service never
+    pauses like that, so the W warm-up steps and K timed steps start from a busy GPU."""
+    n_copies = len(caches)
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(32):
+            ob.decode_attn_partial(caches[i % n_copies], q, ws, splits, stream=stream)
+            ob.decode_attn_reduce(caches[i % n_copies], out, ws, splits, stream=stream)
+            i += 1
+        torch.cuda.synchronize()
+    return i
+
+
 def run_steps(args_steps, warmup, w, cfg, caches, q, new_k, new_v, out, ws, splits, np, torch, ob, stream):
     """warmup untimed steps, then exactly args_steps timed ones between synchronizations.  A step
     is one oscar_decode_step call (append one token per sequence + attention).  Every EV_EVERY-th
@@ -244,19 +266,21 @@ def run_steps(args_steps, warmup, w, cfg, caches, q, new_k, new_v, out, ws, spli
         ob.decode_step(caches[i % n_copies], new_k[i], new_v[i], q, out, ws, splits, hint,
                        stream=stream, timer=ev)
 
-    # the first event-carrying launch of a process pays a one-time host cost (tens of ms when
-    # the previous process's memory is still being reclaimed): take it in the warm-up
+    # Everything the timed region needs on the host exists before the warm-up steps, so that
+    # nothing but the synchronization separates the last warm-up step from the first timed one
+    # (a GPU left idle for a few milliseconds runs the next kernels several per cent slower).
+    # The first event-carrying launch of a process pays a one-time host cost (tens of ms when
+    # the previous process's memory is still being reclaimed): it is taken in the warm-up.
     warm_ev = ob.Timer()
-    for i in range(warmup):
-        step(i, warm_ev if i == 0 else None)
-    if warmup == 0:
-        ob.decode_attn_partial(caches[0], q, ws, splits, stream=stream, timer=warm_ev)
-    torch.cuda.synchronize()
-    warm_ev.close()
     evs = [ob.Timer() if i % EV_EVERY == 0 else None for i in range(args_steps)]
     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     g0.record(stream)       # events are created at their first record: keep that, and whatever
     g1.record(stream)       # else a first use costs on the host, outside the timed region
+    heat_launches = preheat(caches, q, out, ws, splits, torch, ob, stream)
+    if warmup == 0:
+        ob.decode_attn_partial(caches[0], q, ws, splits, stream=stream, timer=warm_ev)
+    for i in range(warmup):
+        step(i, warm_ev if i == 0 else None)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     g0.record(stream)
@@ -267,13 +291,13 @@ def run_steps(args_steps, warmup, w, cfg, caches, q, new_k, new_v, out, ws, spli
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     k_samples = [e.elapsed_us() for e in evs if e is not None]
-    for e in evs:
+    for e in evs + [warm_ev]:
         if e is not None:
             e.close()
     assert all(int(c.dev_status.item()) == 0 for c in caches)
     return {"us_step": wall / args_steps * 1e6, "span_us": g0.elapsed_time(g1) * 1e3 / args_steps,
             "enqueue_us": t_enq / args_steps * 1e6, "k_us": float(np.mean(k_samples)),
-            "k_samples": len(k_samples)}
+            "k_samples": len(k_samples), "preheat_launches": heat_launches}
 
 
 def step_inputs(w, io, total_steps, torch, ob):
@@ -533,6 +557,8 @@ def measure(args, w, np, torch, ob, synth):
                    "l2_cache_mib": round(getattr(prop, "L2_cache_size", 0) / 2**20, 1)},
         "compression_vs_16bit": 2 * w.head_dim * 2 / bytes_tok,
         "separate_region_kernel_us": sep_us,
+        "preheat": {"seconds": PREHEAT_S, "attention_launches": r["preheat_launches"],
+                    "what": "decode-attention launches without appends, right before the warm-up steps (GPU clocks ramp)"},
         "kernel_event_samples_in_timed_region": r["k_samples"],
         "quantize_append_prefill": {"tokens": w.batch * w.context, "us": pre_us,
                                     "hbm_gbs": pre_bytes / (pre_us * 1e-6) / 1e9,

@@ -85,6 +85,24 @@ __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, dpp_mov<0x140>(v));  // row_mirror
   return v;
 }
+// The same reductions with the permutation folded into the max itself, for the page loop
+// (the compiler's form is a move, a canonicalizing max and the max: three instructions a step).
+// A DPP operand must not be read in the two issue slots after the register was written: each
+// step starts with that wait, which the compiler cannot add inside the block.
+#define OSCAR_DPP_MAX_STEPS(OP)                                                              \
+  asm volatile("s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t" \
+               "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t" \
+               "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"     \
+               "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"                \
+               : "+v"(v))
+__device__ __forceinline__ float row16_max_fast(float v) {   // no NaN among the inputs
+  OSCAR_DPP_MAX_STEPS("v_max_f32_dpp");
+  return v;
+}
+__device__ __forceinline__ uint32_t row16_max_u32(uint32_t v) {
+  OSCAR_DPP_MAX_STEPS("v_max_u32_dpp");
+  return v;
+}
 __device__ __forceinline__ float row16_sum(float v) {
   v += dpp_mov<0xB1>(v);
   v += dpp_mov<0x4E>(v);
@@ -423,11 +441,6 @@ __device__ __forceinline__ uint4 pk_max4(const uint4& a, const uint4& b) {
   return make_uint4(pk_max_u16(a.x, b.x), pk_max_u16(a.y, b.y), pk_max_u16(a.z, b.z),
                     pk_max_u16(a.w, b.w));
 }
-__device__ __forceinline__ float max8_halves(const uint4& r) {
-  const uint32_t m = pk_max_u16(pk_max_u16(r.x, r.y), pk_max_u16(r.z, r.w));
-  const uint32_t t = max(m & 0xffffu, m >> 16);
-  return __half2float(__ushort_as_half((unsigned short)t));
-}
 
 // rows of the 16-row operand tile: head h -> hi row 4*(h%4) + 2*(h/4), lo row + 1, so the
 // accumulator lane group q4 (rows 4*q4..4*q4+3) owns heads q4 (slot 0) and q4+4 (slot 1).
@@ -764,6 +777,17 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         for (int kk = 0; kk < 4; ++kk)
           areg[kk] = *reinterpret_cast<const half8*>(&A_tab[n][32 * q4 + 8 * kk]);
         wave_lds_fence();
+        // logits of a tile pair: read one pair late, behind the next pair's matrix instructions,
+        // so that nothing waits for an accumulator that is still in the matrix pipe
+        auto logits = [&](int T, const float4v& a0, const float4v& a1) {
+#pragma unroll
+          for (int s = 0; s < HP; ++s) {
+            // T is even: tokens T, T+1 are the two halves of norm word T/2
+            S[s][T] = mix_scale<0>(fmaf(a0[2 * s] + a0[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
+            S[s][T + 1] = mix_scale<1>(fmaf(a1[2 * s] + a1[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
+          }
+        };
+        float4v prev0, prev1;
 #pragma unroll
         for (int tt = 0; tt < TPG; tt += 2) {
           // two token tiles at a time: independent accumulators keep the MFMA pipe busy
@@ -800,13 +824,11 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
               acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(
                   areg[kk], __builtin_bit_cast(half8, b0[kk]), acc1, 0, 0, 0);
           }
-#pragma unroll
-          for (int s = 0; s < HP; ++s) {
-            // T is even: tokens T, T+1 are the two halves of norm word T/2
-            S[s][T] = mix_scale<0>(fmaf(acc0[2 * s] + acc0[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
-            S[s][T + 1] = mix_scale<1>(fmaf(acc1[2 * s] + acc1[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
-          }
+          if (tt > 0) logits(T - 2, prev0, prev1);
+          prev0 = acc0;
+          prev1 = acc1;
         }
+        logits(g * TPG + TPG - 2, prev0, prev1);
       }
     }
     kr.load_norm(nx, lane);
@@ -819,7 +841,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
       float mx = S[s][0];
 #pragma unroll
       for (int T = 1; T < 8; ++T) mx = fmaxf(mx, S[s][T]);
-      const float m_new = fmaxf(m_run[s], row16_max(mx));
+      const float m_new = fmaxf(m_run[s], row16_max_fast(mx));
       alpha[s] = __builtin_amdgcn_exp2f(m_run[s] - m_new);
       rescale |= (m_new != m_run[s]);
       m_run[s] = m_new;
@@ -836,12 +858,11 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     uint4 dm = vr.vd[0];
 #pragma unroll
     for (int g = 1; g < NGV; ++g) dm = pk_max4(dm, vr.vd[g]);
-    float dmax = max8_halves(dm);
-    dmax = row16_max(dmax);   // the 16 lanes of a head group cover all 128 tokens
-    int exv = 0;
-    (void)frexpf(dmax, &exv);
-    if (!(dmax > 0.0f) || isinf(dmax)) exv = 0;
-    const int xv = 13 - exv;
+    // Step sizes are non-negative fp16 numbers: the largest has the largest bit pattern, and its
+    // exponent field E bounds it by 2^(E - 14) (2^-14 for E = 0: zero or subnormal steps)
+    const uint32_t dm2 = pk_max_u16(pk_max_u16(dm.x, dm.y), pk_max_u16(dm.z, dm.w));
+    const uint32_t dbits = row16_max_u32(max(dm2 & 0xffffu, dm2 >> 16));  // the 16 lanes of a head group cover all 128 tokens
+    const int xv = 27 - (int)(dbits >> 10);
     rescale |= (xv != xv_cur);
     if (__any(rescale)) {
       float f[HP];

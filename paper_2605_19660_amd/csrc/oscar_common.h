@@ -156,8 +156,11 @@ void oscar_launch_decode_reduce(const float* ws, void* out, int num_splits, int 
 // Resident workgroups per CU of the matrix-core decode kernel for a variant (bits, head slots,
 // key groups per page, value groups); the launch bounds and the split heuristic share it.
 __host__ __device__ constexpr int oscar_decode_mfma_wgs_per_cu(int bits, int hp, int ngk, int ngv) {
-  if (hp == 1) return (bits == 4 && (ngk == 4 || (ngk == 2 && ngv == 4))) ? 1 : 2;
-  if (bits == 2) return (ngv == 4 && ngk >= 2) ? 1 : 2;
+  // (measured, partial pass in us at one / two per CU: (4,1,4,4) 65 / 73 with 13 registers in
+  // scratch, (4,2,1,4) 35 / 38, (4,2,2,4) 37 / 43; the other way round (2,2,4,4) 39 / 33,
+  // (2,2,2,4) 34 / 30, (4,1,2,4) 62 / 60, (4,1,4,1) 62 / 59, (4,1,4,2) 63 / 61)
+  if (hp == 1) return (bits == 4 && ngk == 4 && ngv == 4) ? 1 : 2;
+  if (bits == 2) return 2;
   return (ngv == 1 && ngk <= 2) ? 2 : 1;
 }
 int oscar_launch_decode_mfma(const void* params, int gq, dim3 grid, hipStream_t st,

@@ -28,9 +28,9 @@ SOURCES = {
 }
 
 
-def _compile(name: str, extra: list[str], verbose: bool) -> str:
+def _compile(name: str, extra: list[str], verbose: bool, tag: str = "") -> str:
     src = os.path.join(CSRC, name)
-    obj = os.path.join(OBJ, name.replace(".hip", ".o"))
+    obj = os.path.join(OBJ, name.replace(".hip", tag + ".o"))
     cmd = ["hipcc", *COMMON, *extra, "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -44,17 +44,37 @@ def _compile(name: str, extra: list[str], verbose: bool) -> str:
     return obj
 
 
+def _link(lib: str, objs: list[str], verbose: bool) -> str:
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return lib
+
+
 def build(verbose: bool = False, jobs: int = 6) -> str:
     os.makedirs(OBJ, exist_ok=True)
     present = {n: e for n, e in SOURCES.items() if os.path.exists(os.path.join(CSRC, n))}
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda kv: _compile(kv[0], kv[1], verbose), present.items()))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return LIB
+    return _link(LIB, objs, verbose)
+
+
+# The same library with phase time stamps in the matrix-core decode kernel (phase_profile.py):
+# only the two translation units of that kernel are compiled again.
+STAMPED = ("oscar_decode_mfma.hip", "oscar_decode_mfma_zpmin.hip")
+LIB_STAMPS = os.path.join(HERE, "liboscar_hip_stamps.so")
+
+
+def build_stamps(verbose: bool = False, jobs: int = 6) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(
+            lambda kv: _compile(kv[0], kv[1] + ["-DOSCAR_DECODE_STAMPS"], verbose, "_stamps")
+            if kv[0] in STAMPED else _compile(kv[0], kv[1], verbose), SOURCES.items()))
+    return _link(LIB_STAMPS, objs, verbose)
 
 
 if __name__ == "__main__":
-    print(build(verbose="-q" not in sys.argv))
+    quiet = "-q" in sys.argv
+    print(build_stamps(verbose=not quiet) if "--stamps" in sys.argv else build(verbose=not quiet))

@@ -57,6 +57,22 @@
 #define OSCAR_DECODE_PRIORITY 1
 #endif
 
+// Phase time stamps (measurement aid, off in the library proper: build.py --stamps makes a
+// second library with them, phase_profile.py runs it).  Lane 0 of every wave of the first and
+// the last four workgroups of the grid writes the constant-rate counter (100 MHz, the same on
+// every CU) at the phase boundaries below; indices are masked, the array is fixed.
+#ifdef OSCAR_DECODE_STAMPS
+namespace {
+__device__ unsigned long long g_stamps[8][4][32];
+}
+#define OSCAR_STAMP(i)                                                                  \
+  do {                                                                                  \
+    if (stamp_on && lane == 0) g_stamps[stamp_slot & 7][wave & 3][(i) & 31] = wall_clock64(); \
+  } while (0)
+#else
+#define OSCAR_STAMP(i)
+#endif
+
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -480,6 +496,16 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   // wave index as a scalar: page numbers and block-table lookups stay on the scalar unit
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, q4 = lane >> 4;
+#ifdef OSCAR_DECODE_STAMPS
+  const bool stamp_first = kvh == 0 && b == 0 && split < 4;
+  const bool stamp_last = kvh == (int)gridDim.y - 1 && b == (int)gridDim.z - 1 && split < 4;
+  const bool stamp_on = stamp_first || stamp_last;
+  const int stamp_slot = (stamp_last ? 4 : 0) + (split & 3);
+#endif
+  OSCAR_STAMP(0);   // entry
+  // highest priority from the start (it falls in the page loop, see there): the workgroup that
+  // reached the CU second should not get its first loads out behind the first one's prologue
+  if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(3);
   const int Hkv = P.c.cfg.n_kv_heads, Hq = P.c.cfg.n_q_heads;
   constexpr bool zp_min = ZPMIN;
 
@@ -496,6 +522,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     const int idx = pg_first + pstride * (it0 + lane);
     return idx < P.c.max_pages_per_seq ? table[idx] : 0;
   };
+  OSCAR_STAMP(1 + (P.num_splits & 0));   // kernel arguments have arrived
   int tab = load_table(0);
   // queries: DPP row q4 of every wave takes head q4 (and q4 + 4 in the second slot), 8
   // channels (channel group cg) per lane; absent heads read as zeros
@@ -542,6 +569,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     kr.load(first, lane);
     vr.load(first, lane);
   }
+  OSCAR_STAMP(2);   // first page's loads issued
 
   // this wave's operand tables start as zeros (rows of absent heads stay zero)
   for (int i = lane; i < 16 * TABW / 8; i += 64) {
@@ -561,6 +589,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     for (int i = 0; i < 8; ++i) qh[s][i] *= P.qk_scale_log2;
   }
 
+  OSCAR_STAMP(3);   // queries rotated
   // ---- wave state: online softmax over this wave's pages, seeded by its residual tokens ----
   float m_run[HP], l_run[HP], bv[HP][NGV];
   float4v O[8];
@@ -699,6 +728,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 
   Masks<BITS> masks;
   masks.init();
+  OSCAR_STAMP(4);   // prologue done
   _Float16(*A_tab)[TABW] = s_A[wave];
   _Float16(*P_tab)[TABW] = s_P[wave];
 
@@ -711,7 +741,6 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   const int n_iter = pg_first < n_pages ? (n_pages - pg_first + pstride - 1) / pstride : 0;
   const int prio_step = max(1, (n_iter + 3) >> 2);
   int prio_next = prio_step, prio_level = 0;
-  if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(3);
 
   // Iterations come in chunks of 64 so that the table register is only reloaded between
   // chunks; tabn (lane 0) is the first entry of the following chunk.
@@ -724,6 +753,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   asm volatile("" ::"v"(tab), "v"(tabn));
   for (int iti = 0; iti < it_end; ++iti) {
     const int pg = pg_first + pstride * (it0 + iti);
+    OSCAR_STAMP(8 + min(it0 + iti, 15));   // top of page iteration 0..15
     if (OSCAR_DECODE_PRIORITY && it0 + iti == prio_next) {
       prio_next += prio_step;
       ++prio_level;
@@ -832,6 +862,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
       }
     }
     kr.load_norm(nx, lane);
+    if (it0 + iti == 0) OSCAR_STAMP(5);   // first page's logits done
 
     // ---- online softmax (per head slot; the 16 lanes of a group share a head) ----
     float alpha[HP];
@@ -958,6 +989,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   }
   }
 
+  OSCAR_STAMP(24);   // page loop done
   if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(0);
   // ---- wave results -> LDS ----
   {
@@ -982,7 +1014,9 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   }
 
   // ---- merge the 4 wave states and the residual state, write the split's record ----
+  OSCAR_STAMP(25);   // wave results in LDS
   __syncthreads();
+  OSCAR_STAMP(26);   // all four waves there
   // a thread owns one channel of every second head (the head parity is wave-uniform, so no
   // lane idles); the reads of a head are independent and go out together
   const int ch = tid & (D - 1), hh = __builtin_amdgcn_readfirstlane(tid >> 7);
@@ -1022,6 +1056,7 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     P.ws[rec * WS_STRIDE + D] = M;
     P.ws[rec * WS_STRIDE + D + 1] = L;
   }
+  OSCAR_STAMP(27);   // split record written
 }
 
 template <int BITS, int HP>
@@ -1074,6 +1109,14 @@ int oscar_launch_decode_mfma_zpmin(const void* params, int gq, dim3 grid, hipStr
 }
 
 #else
+
+#ifdef OSCAR_DECODE_STAMPS
+// [8 workgroup slots][4 waves][32 stamps] of the last stamped launch (integer zero-point variants)
+extern "C" int oscar_debug_read_stamps(void* dst, size_t bytes) {
+  if (!dst || bytes != sizeof(g_stamps)) return OSCAR_ERR_INVALID_ARG;
+  return hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_stamps), sizeof(g_stamps)) == hipSuccess ? OSCAR_OK : OSCAR_ERR_HIP;
+}
+#endif
 
 int oscar_launch_decode_mfma_zpmin(const void* params, int gq, dim3 grid, hipStream_t st,
                                    hipEvent_t e0, hipEvent_t e1);

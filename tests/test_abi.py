@@ -147,3 +147,18 @@ def test_cache_layer_views_are_plain_pointer_arithmetic():
     assert ob.lib().oscar_cache_layer(None, L, 0, C.byref(view)) == ob.ERR_INVALID_ARG
     allc.tickets = None                      # optional pointers stay NULL in the view
     assert ob.lib().oscar_cache_layer(C.byref(allc), L, 2, C.byref(view)) == ob.OK and not view.tickets
+
+
+def test_time_stamped_variant_exports_the_same_entry_points_and_its_reader():
+    """The library phase_profile.py runs (built by `build.py --stamps`) is the product library plus
+    one reader for the stamps; no compute call here."""
+    path = os.path.join(os.path.dirname(ob.LIB_PATH), "liboscar_hip_stamps.so")
+    if not os.path.exists(path):
+        pytest.skip("liboscar_hip_stamps.so not built (python -m paper_2605_19660_amd.build --stamps)")
+    lib = C.CDLL(path)
+    for name in ob.EXPORTS:
+        assert hasattr(lib, name), name
+    lib.oscar_debug_read_stamps.argtypes = [C.c_void_p, C.c_size_t]
+    lib.oscar_debug_read_stamps.restype = C.c_int
+    assert lib.oscar_debug_read_stamps(None, 0) == ob.ERR_INVALID_ARG
+    assert not hasattr(ob.lib(), "oscar_debug_read_stamps")

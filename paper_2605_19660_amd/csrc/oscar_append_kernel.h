@@ -651,18 +651,15 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     for (int p = 0; p < 8; ++p) {
       float v[8];
       vraw[p].widen(v);
-      float mn = v[0], mx = v[0];
-#pragma unroll
-      for (int e = 1; e < 8; ++e) {
-        mn = fminf(mn, v[e]);
-        mx = fmaxf(mx, v[e]);
-      }
-      mn = fminf(mn, partner<0>(mn)); mx = fmaxf(mx, partner<0>(mx));
-      mn = fminf(mn, partner<1>(mn)); mx = fmaxf(mx, partner<1>(mx));
-      if (L > 4) { mn = fminf(mn, partner<2>(mn)); mx = fmaxf(mx, partner<2>(mx)); }
-      if (L > 8) { mn = fminf(mn, partner<3>(mn)); mx = fmaxf(mx, partner<3>(mx)); }
-      vmn[p] = mn;
-      vmx[p] = mx;
+      const float mn = min_finite(min3_finite(min3_finite(v[0], v[1], v[2]), v[3], v[4]),
+                                  min3_finite(v[5], v[6], v[7]));
+      const float mx = max_finite(max3_finite(max3_finite(v[0], v[1], v[2]), v[3], v[4]),
+                                  max3_finite(v[5], v[6], v[7]));
+      float rmn = partner_min<1>(partner_min<0>(mn)), rmx = partner_max<1>(partner_max<0>(mx));
+      if (L > 4) { rmn = partner_min<2>(rmn); rmx = partner_max<2>(rmx); }
+      if (L > 8) { rmn = partner_min<3>(rmn); rmx = partner_max<3>(rmx); }
+      vmn[p] = rmn;
+      vmx[p] = rmx;
     }
     // The 4 lanes of a quad always share a value group: lane j of the quad works out the
     // Eq. 3-4 parameters of passes 2j and 2j+1 and the quad reads them back by broadcast.

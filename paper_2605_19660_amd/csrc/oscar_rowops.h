@@ -15,6 +15,48 @@ template <int STAGE> __device__ __forceinline__ float partner(float v) {
   return __builtin_bit_cast(
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true));
 }
+// min / max of finite values as the bare instructions: fminf / fmaxf put a canonicalizing
+// v_max_f32 x, x in front of every operand the compiler cannot prove to be no signalling NaN
+// (anything that came out of a load or a DPP move), and the reduction over partners becomes a
+// move, two of those and the operation.  For numbers the results are the same bits (-0 < +0
+// either way).  A DPP operand must not be read in the two issue slots after it was written:
+// the partner forms start with that wait, which the compiler cannot add inside the block.
+__device__ __forceinline__ float min_finite(float a, float b) {
+  float r;
+  asm volatile("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float max_finite(float a, float b) {
+  float r;
+  asm volatile("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float min3_finite(float a, float b, float c) {
+  float r;
+  asm volatile("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float max3_finite(float a, float b, float c) {
+  float r;
+  asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+#define OSCAR_PARTNER_OP(NAME, OP)                                                                      \
+  template <int STAGE> __device__ __forceinline__ float NAME(float v) {                                 \
+    float r;                                                                                            \
+    if (STAGE == 0)                                                                                     \
+      asm volatile("s_nop 1\n\t" OP " %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v)); \
+    else if (STAGE == 1)                                                                                \
+      asm volatile("s_nop 1\n\t" OP " %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v)); \
+    else if (STAGE == 2)                                                                                \
+      asm volatile("s_nop 1\n\t" OP " %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));     \
+    else                                                                                                \
+      asm volatile("s_nop 1\n\t" OP " %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));           \
+    return r;                                                                                           \
+  }
+OSCAR_PARTNER_OP(partner_min, "v_min_f32_dpp")   // min(v, partner<STAGE>(v))
+OSCAR_PARTNER_OP(partner_max, "v_max_f32_dpp")
+#undef OSCAR_PARTNER_OP
 __device__ __forceinline__ int channel_group_of_row_lane(int r) {
   const int b2 = (r >> 2) & 1;
   return ((r ^ b2) & 1) | ((((r >> 1) ^ b2) & 1) << 1) | (b2 << 2) | (r & 8);

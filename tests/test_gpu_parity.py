@@ -830,3 +830,44 @@ def test_three_layers_share_one_block_table():
     view = ob.CCache()
     assert ob.lib().oscar_cache_layer(C.byref(ml._c), L, L, C.byref(view)) == ob.ERR_INVALID_ARG
     assert ob.lib().oscar_cache_layer(C.byref(ml._c), 0, 0, C.byref(view)) == ob.ERR_INVALID_ARG
+
+
+def test_cache_state_is_its_buffers_copy_and_resume():
+    """Checkpoint and resume: the whole state of a cache is the bytes of its buffers (pools,
+    residual window, lengths, block table).  Copied through host memory into a second cache's
+    freshly allocated buffers, it decodes to the same bits, and both caches stay identical bit for
+    bit through further decode steps, a page flush included; the resumed one still matches the
+    oracle."""
+    torch = _torch()
+    ob = _ob()
+    n0, steps = 128 * 3 + 120, 20            # the flush comes 8 steps in
+    w = synth.LLAMA8B_32K.replace(batch=3, n_q_heads=8, n_kv_heads=2, context=n0 + steps)
+    k, v = synth.make_kv_batch(w)
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads)
+    perm = np.random.default_rng(5).permutation(w.batch * 6)
+    a = ob.Cache(cfg, w.batch, 6, page_perm=perm)
+    ref = OracleCache(OracleConfig(), w.batch, w.n_kv_heads, 6 * 128)
+    ob.quantize_append(a, to_dev(k[:, :n0], w.io_dtype), to_dev(v[:, :n0], w.io_dtype), max_seq_len_hint=0)
+    ref.append(k[:, :n0], v[:, :n0])
+    names = ("k_codes", "k_meta", "k_norms", "v_codes", "v_meta", "res_k", "res_v", "res_norm",
+             "block_table", "seq_lens", "res_lens")
+    saved = {n: getattr(a, n).cpu().numpy().copy() for n in names}      # the checkpoint
+    b = ob.Cache(cfg, w.batch, 6)
+    for n in names:
+        getattr(b, n).copy_(torch.from_numpy(saved[n]).to(getattr(b, n).device))
+    splits = 2
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    oa = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    obuf = torch.zeros_like(oa)
+    for t in range(steps):
+        q = to_dev(synth.make_q(w, 300 + t), w.io_dtype)
+        kn, vn = to_dev(k[:, n0 + t:n0 + t + 1], w.io_dtype), to_dev(v[:, n0 + t:n0 + t + 1], w.io_dtype)
+        ob.decode_step(a, kn, vn, q, oa, ws, splits, n0 + t + 1)
+        ob.decode_step(b, kn, vn, q, obuf, ws, splits, n0 + t + 1)
+        ref.append(k[:, n0 + t:n0 + t + 1], v[:, n0 + t:n0 + t + 1])
+        assert np.array_equal(oa.cpu().numpy(), obuf.cpu().numpy()), t
+    assert_decode_close(obuf.cpu().numpy(), ref.decode_attn(synth.make_q(w, 300 + steps - 1)))
+    for n in names:
+        assert np.array_equal(getattr(a, n).cpu().numpy(), getattr(b, n).cpu().numpy()), n
+    assert_cache_equal(b, ref, w)
+    assert int(b.dev_status.item()) == 0

@@ -217,6 +217,15 @@ template <int BITS> struct Masks {
   }
 };
 
+// All four registers of a matrix-instruction result stay allocated up to this point, also the
+// ones nobody reads (rows of absent heads).  Without it the register allocator hands such a
+// register to the next value while the instruction that will still write it is in flight; for
+// its own instructions the compiler then inserts the wait states the hardware asks for, for the
+// instructions inside an asm block it cannot -- and the result of a block placed there was
+// overwritten when the matrix instruction retired (seen as run-to-run differences of a build
+// whose only change was the order of the matrix instructions).
+__device__ __forceinline__ void keep_tuple(const float4v& t) { asm volatile("" ::"v"(t)); }
+
 // One 32-code chunk -> the four B-operand vectors (k-steps 0..3) of a 16x16x32 MFMA.
 template <int BITS> struct Chunk;
 template <> struct Chunk<2> {
@@ -816,6 +825,8 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
             S[s][T] = mix_scale<0>(fmaf(a0[2 * s] + a0[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
             S[s][T + 1] = mix_scale<1>(fmaf(a1[2 * s] + a1[2 * s + 1], ps[s], -bias[s]), nt[T >> 1]);
           }
+          keep_tuple(a0);
+          keep_tuple(a1);
         };
         float4v prev0, prev1;
 #pragma unroll
@@ -989,6 +1000,8 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   }
   }
 
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) keep_tuple(O[ct]);
   OSCAR_STAMP(24);   // page loop done
   if (OSCAR_DECODE_PRIORITY) __builtin_amdgcn_s_setprio(0);
   // ---- wave results -> LDS ----

@@ -871,3 +871,44 @@ def test_cache_state_is_its_buffers_copy_and_resume():
         assert np.array_equal(getattr(a, n).cpu().numpy(), getattr(b, n).cpu().numpy()), n
     assert_cache_equal(b, ref, w)
     assert int(b.dev_status.item()) == 0
+
+
+@pytest.mark.parametrize("bits,context", [(2, 32768), (4, 16384)])
+def test_decode_is_reproducible_launch_after_launch(bits, context):
+    """The decode output of one cache and one query is the same bits on every launch, at a size
+    that fills the chip (two workgroups per CU), with residual tokens, warm and cold.  (A build
+    in which the output of an asm block had been placed on a register that a matrix instruction
+    still in flight was going to write differed from launch to launch; the kernels keep such
+    registers allocated now, and tests/test_asm_hazards.py scans the compiler's output for it.)"""
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(context=context, bits=bits)
+    cfg = ob.Config(w.n_q_heads, w.n_kv_heads, bits=bits)
+    kd, vd = synth.make_kv_device(w)
+    c = ob.Cache(cfg, w.batch, context // 128 + 2)
+    ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    for _ in range(37):
+        kn = torch.randn(w.batch, 1, w.n_kv_heads, 128, device="cuda", generator=g).to(torch.bfloat16)
+        vn = torch.randn(w.batch, 1, w.n_kv_heads, 128, device="cuda", generator=g).to(torch.bfloat16)
+        ob.quantize_append(c, kn, vn, max_seq_len_hint=context + 64)
+    del kd, vd
+    q = to_dev(synth.make_q(w), w.io_dtype)
+    splits = ob.decode_auto_splits(cfg, w.batch, context + 64)
+    ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    junk = torch.empty(384 << 20, dtype=torch.uint8, device="cuda")
+    first, differing = None, 0
+    for i in range(60):
+        if i % 4 == 0:
+            junk.fill_(i & 255)            # push the cache out of the last-level cache now and then
+        ob.decode_attn_partial(c, q, ws, splits)
+        ob.decode_attn_reduce(c, out, ws, splits)
+        o = out.clone()
+        if first is None:
+            first = o
+        elif not torch.equal(o, first):
+            differing += 1
+    assert differing == 0
+    assert int(c.dev_status.item()) == 0

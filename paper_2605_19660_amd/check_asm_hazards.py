@@ -15,8 +15,8 @@ consumed (`keep_tuple`), and this scan checks the compiler's output for what is 
     for every v_mfma: walk forward; an instruction that READS one of its destination registers
     (a dependent matrix instruction or a compiler-scheduled vector instruction, for which the
     compiler has inserted the wait states) proves that it has retired and ends the walk; an
-    instruction inside ASMSTART/ASMEND that WRITES one of them earlier, within `window` wait
-    states, is reported.
+    instruction inside ASMSTART/ASMEND that writes (or reads) one of them earlier, within
+    `window` wait states, is reported.
 """
 from __future__ import annotations
 
@@ -84,12 +84,14 @@ def scan(asm_text: str, window: int = WINDOW) -> list[tuple]:
                 is_store = op.startswith(("ds_write", "buffer_store", "global_store"))
                 reads = set().union(*ops[1:]) if len(ops) > 1 and not is_store else set().union(*ops) if is_store else set()
                 writes = set() if is_store else ops[0]
-                if in_asm[j] and (writes & pending):
-                    found.append((kernel, i + 1, t, j + 1, tj, waited))
-                if reads & pending:
-                    pending = set()              # a guarded read of any result register: the
-                    break                        # instruction has retired, all of them are written
-                pending -= writes                # rewritten by an instruction the compiler guards
+                if in_asm[j] and ((writes | reads) & pending):
+                    found.append((kernel, i + 1, t, j + 1, tj, waited))   # (a read is no better)
+                    pending -= writes | reads
+                elif reads & pending:
+                    break                        # a guarded read of any result register: the
+                                                 # instruction has retired, all of them are written
+                else:
+                    pending -= writes            # rewritten by an instruction the compiler guards
             waited += int(tj.split()[1]) + 1 if op == "s_nop" else 1
             if waited > window or not pending:
                 break

@@ -173,8 +173,10 @@ __device__ __forceinline__ void mul_split_hi_lo(const float (&x)[8], const uint4
 }
 
 // Products of packed fp16 pairs in fp32, and fp16 * fp32, without widening instructions:
-// the mixed-precision FMA reads fp16 sources in place.  (All of these blocks are volatile:
-// as plain asm the (32,32)-group kernel came out with wrong logits.)
+// the mixed-precision FMA reads fp16 sources in place.  (The wrong logits that a (32,32)-group
+// build once showed with these blocks as plain asm came from an output register placed on the
+// destination of a matrix instruction in flight, see keep_tuple; with that fixed they work as
+// plain asm too, and stay volatile only because nothing is gained by letting them move.)
 __device__ __forceinline__ void mix_mul_pair(uint32_t a, uint32_t b, float& lo, float& hi) {
   asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,1,0]" : "=v"(lo) : "v"(a), "v"(b));
   asm volatile("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(hi) : "v"(a), "v"(b));

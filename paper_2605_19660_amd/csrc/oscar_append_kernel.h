@@ -52,13 +52,22 @@ namespace {
 constexpr int D = OSCAR_D;
 constexpr int R = OSCAR_R;
 
+// 16 bytes of the caller's K / V, which this launch reads exactly once: a non-temporal load
+// (measured on a kernel that only moves the encoder's bytes in the encoder's pattern: 223 us
+// against 254 us with plain loads for the 1.07 GB + 0.2 GB of a 262144-token prefill)
+__device__ __forceinline__ uint4 load_once(const void* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Eight consecutive elements of the caller's type, held raw (packed) in registers.
 template <typename IO> struct Raw8;
 template <> struct Raw8<float> {
   uint4 a, b;
   __device__ __forceinline__ void load(const float* p) {
-    a = reinterpret_cast<const uint4*>(p)[0];
-    b = reinterpret_cast<const uint4*>(p)[1];
+    a = load_once(p);
+    b = load_once(p + 4);
   }
   __device__ __forceinline__ void load_halves(const __half* p) {   // 8 fp16 values, kept in a
     a = *reinterpret_cast<const uint4*>(p);
@@ -85,16 +94,14 @@ __device__ __forceinline__ void widen_halves(const uint4& r, float (&x)[8]) {
 }
 template <> struct Raw8<__half> {
   uint4 a;
-  __device__ __forceinline__ void load(const __half* p) { a = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void load(const __half* p) { a = load_once(p); }
   __device__ __forceinline__ void load_halves(const __half* p) { load(p); }
   __device__ __forceinline__ void store(__half* p) const { *reinterpret_cast<uint4*>(p) = a; }
   __device__ __forceinline__ void widen(float (&x)[8]) const { widen_halves(a, x); }
 };
 template <> struct Raw8<__hip_bfloat16> {
   uint4 a;
-  __device__ __forceinline__ void load(const __hip_bfloat16* p) {
-    a = *reinterpret_cast<const uint4*>(p);
-  }
+  __device__ __forceinline__ void load(const __hip_bfloat16* p) { a = load_once(p); }
   __device__ __forceinline__ void load_halves(const __half* p) {
     a = *reinterpret_cast<const uint4*>(p);
   }

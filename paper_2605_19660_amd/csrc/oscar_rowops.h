@@ -68,8 +68,26 @@ __device__ __forceinline__ void butterfly_signs(int cg, uint32_t (&sgn)[4]) {
 }
 
 // H(x)/sqrt(128) of the 8 channels a lane holds.  Butterfly stage h pairs (i, i|h):
-// lower <- a+b, upper <- a-b; across lanes that is partner + own, with the own value negated
-// in the upper lane -- the same fp32 additions and subtractions, in stage order 1, 2, ..., 64.
+// lower <- a+b, upper <- a-b, in stage order 1, 2, ..., 64.  The four stages across lanes are one
+// instruction per element: own += partner * s with s = +1 in the lower lane and -1 in the upper
+// one (a fused multiply-add whose product is exact, so the sum is rounded once like the add or
+// subtract it stands for).  The upper lane then holds b - a, the negative of what the order
+// prescribes; both lanes of every later pair carry the same accumulated sign, so each stage
+// again produces plus or minus the prescribed value, and the sign a lane has collected --
+// minus for an odd number of set bits in its channel group -- goes into the 1/sqrt(128) factor.
+// Negation commutes with rounding: the results are the prescribed numbers (an exact zero can
+// come out with the other sign, which no consumer can tell).  A DPP operand must not be read in
+// the two issue slots after it was written: the block starts with that wait, and inside it every
+// element is rewritten eight instructions before it is read again.
+#define OSCAR_BFLY_STAGE(S, CTRL)                                            \
+  "v_fmac_f32_dpp %0, %0, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %1, %1, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %2, %2, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %3, %3, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %4, %4, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %5, %5, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %6, %6, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"      \
+  "v_fmac_f32_dpp %7, %7, " S " " CTRL " row_mask:0xf bank_mask:0xf\n\t"
 __device__ __forceinline__ void rotate8(float (&x)[8], const uint32_t (&sgn)[4]) {
 #pragma unroll
   for (int h = 1; h < 8; h <<= 1) {
@@ -82,15 +100,18 @@ __device__ __forceinline__ void rotate8(float (&x)[8], const uint32_t (&sgn)[4])
       }
     }
   }
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<0>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[0]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<1>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[1]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<2>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[2]);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = partner<3>(x[i]) + __uint_as_float(__float_as_uint(x[i]) ^ sgn[3]);
-  const float c = 0.08838834764831845f;  // fp32(1/sqrt(128))
+  const float s0 = __uint_as_float(0x3f800000u | sgn[0]), s1 = __uint_as_float(0x3f800000u | sgn[1]);
+  const float s2 = __uint_as_float(0x3f800000u | sgn[2]), s3 = __uint_as_float(0x3f800000u | sgn[3]);
+  asm volatile("s_nop 1\n\t"
+               OSCAR_BFLY_STAGE("%8", "quad_perm:[1,0,3,2]")
+               OSCAR_BFLY_STAGE("%9", "quad_perm:[2,3,0,1]")
+               OSCAR_BFLY_STAGE("%10", "row_half_mirror")
+               OSCAR_BFLY_STAGE("%11", "row_ror:8")
+               : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+               : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+  // fp32(1/sqrt(128)), with the lane's collected sign
+  const float c = __uint_as_float(0x3db504f3u ^ sgn[0] ^ sgn[1] ^ sgn[2] ^ sgn[3]);
 #pragma unroll
   for (int i = 0; i < 8; ++i) x[i] = x[i] * c;
 }
+#undef OSCAR_BFLY_STAGE

@@ -20,6 +20,7 @@ SOURCES = {
     "oscar_api.hip": [],
     "oscar_quantize.hip": ["-ffp-contract=off"],
     "oscar_quantize_allheads.hip": ["-ffp-contract=off"],
+    "oscar_quantize_switched.hip": ["-ffp-contract=off"],
     "oscar_decode.hip": [],
     "oscar_decode_mfma.hip": [],
     "oscar_decode_mfma_zpmin.hip": [],

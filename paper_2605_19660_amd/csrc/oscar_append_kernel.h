@@ -42,9 +42,14 @@ struct AppendParams {
   uint32_t flags;
 };
 
-// The encoder instantiations with one norm over all kv heads (and the norm pre-pass they
-// need) live in a translation unit of their own: the two sets compile side by side and the
-// default path's register allocation does not depend on the variant's code.
+// Three sets of encoder instantiations, each in a translation unit of its own (they compile
+// side by side, and the register allocation of the published method does not depend on the
+// variants' code):
+//   XF_PUBLISHED  rotation on, L2 norm per (token, kv head): the switches are constants
+//   XF_SWITCHED   rotation and scaling coefficient read from the configuration (the ablations)
+//   XF_ALL_HEADS  one norm over all kv heads, with the norm pre-pass it needs
+constexpr int XF_PUBLISHED = 0, XF_SWITCHED = 1, XF_ALL_HEADS = 2;
+int oscar_launch_append_switched(const AppendParams& P, dim3 grid, hipStream_t st);
 int oscar_launch_append_all_heads(const AppendParams& P, dim3 grid, hipStream_t st);
 
 namespace {
@@ -216,6 +221,61 @@ __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// value of row lane r ^ 4: lanes 0-3 and 8-11 read four lanes up, the others four lanes down
+__device__ __forceinline__ float same_position_next_quad(float v) {
+  const int x = __builtin_bit_cast(int, v);
+  int t = __builtin_amdgcn_update_dpp(0, x, 0x104 /* row_shl:4 */, 0xf, 0x5, false);
+  t = __builtin_amdgcn_update_dpp(t, x, 0x114 /* row_shr:4 */, 0xf, 0xa, false);
+  return __builtin_bit_cast(float, t);
+}
+
+// The published transform (rotation, L2 norm) of four tokens held by the same 16-lane row.
+// The cross-lane part of the four sums of squares is a reduce-scatter over the quad followed
+// by an all-reduce over the row's four quads (whose lanes hold channel groups that differ in
+// bits 2 and 3): in the first stage a lane passes on the two
+// sums its partner keeps and adds what it receives to the two it keeps, in the second stage
+// one of one -- the additions of the balanced tree, operands in either order -- so that the
+// lane at quad position j ends up with the complete sum of token j and takes one square root
+// and one reciprocal for it; the four reciprocals come back by quad broadcast.
+// n_own: the stored norm of token `qj` (the caller's position in its quad).
+template <typename META>
+__device__ __forceinline__ void key_transform_4tokens(float (&x)[4][8], const uint32_t (&sgn)[4],
+                                                      int qj, float& n_own, uint4* ku) {
+  float s[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    rotate8(x[j], sgn);
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = x[j][i] * x[j][i];
+    s[j] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+  }
+  const bool odd = (qj & 1) != 0, high = (qj & 2) != 0;
+  const float k01 = odd ? s[1] : s[0], g01 = odd ? s[0] : s[1];
+  const float k23 = odd ? s[3] : s[2], g23 = odd ? s[2] : s[3];
+  const float t01 = k01 + partner<0>(g01);   // token 0 (even lanes) or 1 (odd lanes)
+  const float t23 = k23 + partner<0>(g23);   // token 2 or 3
+  const float kk = high ? t23 : t01, gg = high ? t01 : t23;
+  float u = kk + partner<1>(gg);             // token qj, summed over this quad's channel groups
+  // The other quad of the half-row holds the channel groups that differ in bit 2; the partner
+  // there must sit at the same quad position (partner<2> mirrors the half-row and would hand
+  // over another token's sum): row lane r ^ 4.
+  u = u + same_position_next_quad(u);
+  u = u + partner<3>(u);                     // row lane r ^ 8
+  const float nf = round_meta<META>(sqrtf(u));
+  const float inv = (nf > 0.0f && !isinf(nf)) ? 1.0f / nf : 0.0f;
+  n_own = nf;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float iv = quad_bcast(inv, j);
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = half_bits(pin_f32(x[j][2 * i] * iv)) | (half_bits(pin_f32(x[j][2 * i + 1] * iv)) << 16);
+    ku[j] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 // Same transform with a norm that is already known (rounded to its storage type).
 __device__ __forceinline__ uint4 key_transform8_given(float (&x)[8], const uint32_t (&sgn)[4],
                                                       float nf, bool rotate) {
@@ -372,8 +432,9 @@ __device__ __forceinline__ void key_codes(const uint4& ku, const float (&rd)[8],
   }
 }
 
-template <typename IO, typename META, int BITS, int KG, bool NORM_ALL>
+template <typename IO, typename META, int BITS, int KG, int XF>
 __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
+  constexpr bool NORM_ALL = XF == XF_ALL_HEADS;
   constexpr int NGK = R / KG;        // key groups per page
   constexpr int PPG = KG / 16;       // passes per key group
   constexpr float QMAX = (float)((1 << BITS) - 1);
@@ -402,7 +463,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   const int cg = channel_group_of_row_lane(tid & 15);   // channels 8*cg .. 8*cg+7
   const int Hkv = P.c.cfg.n_kv_heads;
   const bool zp_min = P.c.cfg.zp_mode == OSCAR_ZP_MIN;
-  const KeyXf xf = key_xf_of(P.c.cfg);
+  const KeyXf xf = XF == XF_PUBLISHED ? KeyXf() : key_xf_of(P.c.cfg);
   uint32_t sgn[4];
 #pragma unroll
   for (int st = 0; st < 4; ++st) sgn[st] = ((cg >> st) & 1) ? 0x80000000u : 0u;
@@ -430,6 +491,10 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
   uint4 ku[8];
   Raw8<IO> vraw[8];
   float nrm[8];
+  // batched_norms (uniform over the workgroup): the norms of tokens 16*(4*hb + j) + slot sit in
+  // nrm_q[hb] of the lanes whose position in their quad is j, and nrm[] is unused
+  bool batched_norms = false;
+  float nrm_q[2] = {0.0f, 0.0f};
   // NORM_ALL: the norms of new tokens that end up in a page were written into that page's
   // norm slots (of every head) by oscar_token_norm_kernel, launched just before this kernel
   const META* pre_norm = nullptr;
@@ -446,10 +511,16 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
     const IO* vp = vnew + (tok0 * Hkv + kvh) * D + cg * 8;
     const size_t pstride = (size_t)16 * Hkv * D;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      kraw[p].load(kp + p * pstride);
-      vraw[p].load(vp + p * pstride);
-    }
+    for (int p = 0; p < 8; ++p) kraw[p].load(kp + p * pstride);
+    // The values are not needed before the key codes are done: their loads go out behind the
+    // first half of the key transform (held there by the fences), which keeps their 32
+    // registers free while the transform is at its widest and spreads the workgroup's requests.
+    auto load_values = [&]() {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int p = 0; p < 8; ++p) vraw[p].load(vp + p * pstride);
+      __builtin_amdgcn_sched_barrier(0);
+    };
     if (NORM_ALL) {
 #pragma unroll
       for (int p = 0; p < 8; ++p) nrm[p] = to_f32<META>(pre_norm[tok_meta_pos(p * 16 + slot)]);
@@ -458,6 +529,19 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
         float x[8];
         kraw[p].widen(x);
         ku[p] = key_transform8_given(x, sgn, nrm[p], xf.rotate);
+        if (p == 3) load_values();
+      }
+    } else if (XF == XF_PUBLISHED) {
+      // the method as published: four tokens at a time, one square root and one reciprocal
+      // per lane instead of four (key_transform_4tokens)
+      batched_norms = true;
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb) {
+        float x[4][8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kraw[4 * hb + j].widen(x[j]);
+        key_transform_4tokens<META>(x, sgn, tid & 3, nrm_q[hb], &ku[4 * hb]);
+        if (hb == 0) load_values();
       }
     } else {
 #pragma unroll
@@ -465,6 +549,7 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
         float x[8];
         kraw[p].widen(x);
         ku[p] = key_transform8<META>(x, sgn, nrm[p], xf);
+        if (p == 3) load_values();
       }
     }
   } else if (do_block) {
@@ -577,7 +662,13 @@ __global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
       s_red[gk][wave][cg].mx = make_uint4(mx[0], mx[1], mx[2], mx[3]);
     }
   }
-  if (cg == 0) {
+  if (batched_norms) {
+    if ((tid & 15) < 4) {   // first quad of the token row: lane j holds the norms of passes j, 4 + j
+#pragma unroll
+      for (int hb = 0; hb < 2; ++hb)
+        s_norm[tok_meta_pos((4 * hb + (tid & 3)) * 16 + slot)] = from_f32<META>(nrm_q[hb]);
+    }
+  } else if (cg == 0) {
 #pragma unroll
     for (int p = 0; p < 8; ++p) s_norm[tok_meta_pos(p * 16 + slot)] = from_f32<META>(nrm[p]);
   }
@@ -804,33 +895,33 @@ __global__ void oscar_update_lens_kernel(AppendParams P) {
   P.c.res_lens[b] = sp.tail_len;
 }
 
-template <typename IO, typename META, int BITS, bool NORM_ALL>
+template <typename IO, typename META, int BITS, int XF>
 int launch_kg(const AppendParams& P, dim3 grid, hipStream_t st) {
   switch (P.g.k_group) {
-    case 32: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 32, NORM_ALL>), grid, dim3(256), 0, st, P); break;
-    case 64: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 64, NORM_ALL>), grid, dim3(256), 0, st, P); break;
-    case 128: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 128, NORM_ALL>), grid, dim3(256), 0, st, P); break;
+    case 32: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 32, XF>), grid, dim3(256), 0, st, P); break;
+    case 64: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 64, XF>), grid, dim3(256), 0, st, P); break;
+    case 128: hipLaunchKernelGGL((oscar_append_kernel<IO, META, BITS, 128, XF>), grid, dim3(256), 0, st, P); break;
     default: return OSCAR_ERR_UNSUPPORTED;
   }
   return OSCAR_OK;
 }
 
-template <typename IO, typename META, bool NORM_ALL>
+template <typename IO, typename META, int XF>
 int launch_bits(const AppendParams& P, dim3 grid, hipStream_t st) {
-  if (P.g.bits == 2) return launch_kg<IO, META, 2, NORM_ALL>(P, grid, st);
-  if (P.g.bits == 4) return launch_kg<IO, META, 4, NORM_ALL>(P, grid, st);
+  if (P.g.bits == 2) return launch_kg<IO, META, 2, XF>(P, grid, st);
+  if (P.g.bits == 4) return launch_kg<IO, META, 4, XF>(P, grid, st);
   return OSCAR_ERR_UNSUPPORTED;
 }
 
-template <typename IO, bool NORM_ALL>
+template <typename IO, int XF>
 int launch_meta(const AppendParams& P, dim3 grid, hipStream_t st) {
   int rc;
   if (P.c.cfg.meta_dtype == OSCAR_F16) {
-    rc = launch_bits<IO, __half, NORM_ALL>(P, grid, st);
+    rc = launch_bits<IO, __half, XF>(P, grid, st);
     if (rc == OSCAR_OK && !P.c.tickets)
       hipLaunchKernelGGL((oscar_update_lens_kernel<__half>), dim3((P.c.batch + 63) / 64), dim3(64), 0, st, P);
   } else {
-    rc = launch_bits<IO, float, NORM_ALL>(P, grid, st);
+    rc = launch_bits<IO, float, XF>(P, grid, st);
     if (rc == OSCAR_OK && !P.c.tickets)
       hipLaunchKernelGGL((oscar_update_lens_kernel<float>), dim3((P.c.batch + 63) / 64), dim3(64), 0, st, P);
   }
@@ -883,13 +974,13 @@ int launch_token_norms(const AppendParams& P, hipStream_t st) {
   return OSCAR_OK;
 }
 
-// every instantiation of the encoder for one norm scope
-template <bool NORM_ALL>
+// every instantiation of the encoder for one of the three sets
+template <int XF>
 int launch_append(const AppendParams& P, dim3 grid, hipStream_t st) {
   switch (P.c.cfg.io_dtype) {
-    case OSCAR_F32: return launch_meta<float, NORM_ALL>(P, grid, st);
-    case OSCAR_BF16: return launch_meta<__hip_bfloat16, NORM_ALL>(P, grid, st);
-    case OSCAR_F16: return launch_meta<__half, NORM_ALL>(P, grid, st);
+    case OSCAR_F32: return launch_meta<float, XF>(P, grid, st);
+    case OSCAR_BF16: return launch_meta<__hip_bfloat16, XF>(P, grid, st);
+    case OSCAR_F16: return launch_meta<__half, XF>(P, grid, st);
     default: return OSCAR_ERR_UNSUPPORTED;
   }
 }

@@ -311,8 +311,12 @@ extern "C" int oscar_quantize_append(const void* k, const void* v, int32_t T,
   const int nblk = (R + T) / R;  // a sequence completes at most this many blocks
   dim3 grid(cache->cfg.n_kv_heads, nblk, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  rc = cache->cfg.norm_scope == OSCAR_NORM_ALL_KV_HEADS ? oscar_launch_append_all_heads(P, grid, st)
-                                                         : launch_append<false>(P, grid, st);
+  if (cache->cfg.norm_scope == OSCAR_NORM_ALL_KV_HEADS)
+    rc = oscar_launch_append_all_heads(P, grid, st);
+  else if (cache->cfg.rotation == OSCAR_ROTATION_ON && cache->cfg.scale_mode == OSCAR_SCALE_L2)
+    rc = launch_append<XF_PUBLISHED>(P, grid, st);
+  else
+    rc = oscar_launch_append_switched(P, grid, st);
   if (rc != OSCAR_OK) return rc;
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
   return OSCAR_OK;

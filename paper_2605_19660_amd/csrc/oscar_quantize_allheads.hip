@@ -18,5 +18,5 @@ int oscar_launch_append_all_heads(const AppendParams& P, dim3 grid, hipStream_t 
       default: return OSCAR_ERR_UNSUPPORTED;
     }
   }
-  return launch_append<true>(P, grid, st);
+  return launch_append<XF_ALL_HEADS>(P, grid, st);
 }

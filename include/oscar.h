@@ -126,8 +126,8 @@ typedef struct oscar_config {
  * dropped for that sequence.
  * tickets (may be NULL): a device int32[1], zeroed once by the caller. With it the last
  * workgroup of oscar_quantize_append to finish also advances seq_lens / res_lens (one
- * launch) and leaves the ticket zero again; without it the length update is a second,
- * tiny launch. */
+ * launch) and leaves the ticket zero again; without it, and for grids of more than 1024
+ * workgroups (prefills), the length update is a second, tiny launch. */
 typedef struct oscar_cache {
   oscar_config cfg;
   int32_t batch;
@@ -201,7 +201,7 @@ size_t oscar_decode_workspace_bytes(const oscar_config *cfg, int32_t batch, int3
  * Updates seq_lens / res_lens on the device. Residual keys are quantized from
  * their stored fp16 values (no second rotation). A sequence that receives no token
  * (T == 0 or new_lens[b] == 0) is left untouched under either rule.
- * One launch (plus the length-update launch without cache->tickets); with
+ * One launch (plus the length-update launch without cache->tickets or for a large grid); with
  * OSCAR_NORM_ALL_KV_HEADS a launch in front computes the norms of the new tokens that
  * move into pages and parks them in those pages' norm slots. */
 int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t *new_lens,

@@ -134,6 +134,14 @@ __device__ __forceinline__ float pin_f32(float x) {
 __device__ __forceinline__ uint32_t half_bits(float x) {
   return (uint32_t)__half_as_ushort(__float2half_rn(x));
 }
+// fp16(a) in the low half, fp16(b) in the high half, both rounded to nearest even: one
+// instruction on this chip (v_cvt_pk_f16_f32)
+__device__ __forceinline__ uint32_t pack_halves(float a, float b) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
 
 // value of lane j (a constant after unrolling) of the caller's quad
 template <int CTRL> __device__ __forceinline__ float dpp_read(float v) {
@@ -216,7 +224,7 @@ __device__ __forceinline__ uint4 key_transform8(float (&x)[8], const uint32_t (&
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    w[i] = half_bits(pin_f32(x[2 * i] * inv)) | (half_bits(pin_f32(x[2 * i + 1] * inv)) << 16);
+    w[i] = pack_halves(pin_f32(x[2 * i] * inv), pin_f32(x[2 * i + 1] * inv));
   n_st = nf;
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
@@ -271,7 +279,7 @@ __device__ __forceinline__ void key_transform_4tokens(float (&x)[4][8], const ui
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      w[i] = half_bits(pin_f32(x[j][2 * i] * iv)) | (half_bits(pin_f32(x[j][2 * i + 1] * iv)) << 16);
+      w[i] = pack_halves(pin_f32(x[j][2 * i] * iv), pin_f32(x[j][2 * i + 1] * iv));
     ku[j] = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
@@ -284,7 +292,7 @@ __device__ __forceinline__ uint4 key_transform8_given(float (&x)[8], const uint3
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    w[i] = half_bits(pin_f32(x[2 * i] * inv)) | (half_bits(pin_f32(x[2 * i + 1] * inv)) << 16);
+    w[i] = pack_halves(pin_f32(x[2 * i] * inv), pin_f32(x[2 * i + 1] * inv));
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
@@ -433,7 +441,7 @@ __device__ __forceinline__ void key_codes(const uint4& ku, const float (&rd)[8],
 }
 
 template <typename IO, typename META, int BITS, int KG, int XF>
-__global__ __launch_bounds__(256) void oscar_append_kernel(AppendParams P) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) == 4 ? (XF == 2 ? 2 : 3) : 4))) void oscar_append_kernel(AppendParams P) {
   constexpr bool NORM_ALL = XF == XF_ALL_HEADS;
   constexpr int NGK = R / KG;        // key groups per page
   constexpr int PPG = KG / 16;       // passes per key group

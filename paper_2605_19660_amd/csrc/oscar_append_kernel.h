@@ -32,6 +32,10 @@
 
 #include "oscar_rowops.h"
 
+#ifndef OSCAR_ENC_EARLY_K
+#define OSCAR_ENC_EARLY_K 1
+#endif
+
 struct AppendParams {
   const void* k;
   const void* v;
@@ -486,6 +490,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
   const bool do_block = blk < sp.nq;
   const bool do_tail = (blk == 0);
   if (!do_block && !do_tail) break;
+  // the page this block goes to, asked for now: behind the barrier below the workgroup would
+  // wait for the answer
+  const int phys = do_block ? P.c.block_table[(size_t)b * P.c.max_pages_per_seq + sp.packed_pages + blk] : 0;
 
   const IO* knew = reinterpret_cast<const IO*>(P.k);
   const IO* vnew = reinterpret_cast<const IO*>(P.v);
@@ -507,7 +514,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
   // norm slots (of every head) by oscar_token_norm_kernel, launched just before this kernel
   const META* pre_norm = nullptr;
   if (NORM_ALL && do_block) {
-    const int phys0 = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + sp.packed_pages + blk];
+    const int phys0 = phys;
     pre_norm = reinterpret_cast<const META*>(reinterpret_cast<const uint8_t*>(P.c.k_norms) +
                                              ((size_t)phys0 * Hkv + kvh) * P.g.k_norms_bytes);
   }
@@ -633,8 +640,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
   if (!do_block) break;
 
   // ---- phase 3: quantize the block held in registers ----
-  const int logical_page = sp.packed_pages + blk;
-  const int phys = P.c.block_table[(size_t)b * P.c.max_pages_per_seq + logical_page];
   const size_t pg = (size_t)phys * Hkv + kvh;
   uint8_t* o_kcodes = reinterpret_cast<uint8_t*>(P.c.k_codes) + pg * P.g.k_codes_bytes;
   META* o_kmeta = reinterpret_cast<META*>(reinterpret_cast<uint8_t*>(P.c.k_meta) + pg * P.g.k_meta_bytes);
@@ -746,6 +751,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
     }
   }
 
+#if OSCAR_ENC_EARLY_K
+  // the key-code image is complete: it leaves now, under the value phase, instead of with
+  // everything else at the end of the workgroup (one more barrier)
+  __syncthreads();
+  {
+    constexpr int NV = IMG / 16;
+    const uint4* ksrc = reinterpret_cast<const uint4*>(&s_kimg[0]);
+    uint4* kdst = reinterpret_cast<uint4*>(o_kcodes);
+#pragma unroll
+    for (int i = tid; i < NV; i += 256) kdst[i] = ksrc[i];
+  }
+#endif
+
   // values: per-token min/max over each group of v_group channels (8 registers, then the
   // 4 | 8 | 16 lanes of the group).  The thread's 8 tokens of one channel are the elements
   // e = pass of k-step kk = slot/4 in chunk (tile = c/16, n = c%16, q4 = slot%4): even
@@ -851,19 +869,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
     uint4* vdst = reinterpret_cast<uint4*>(o_vcodes);
 #pragma unroll
     for (int i = tid; i < NV; i += 256) {
+#if !OSCAR_ENC_EARLY_K
       kdst[i] = ksrc[i];
+#endif
       vdst[i] = vsrc[i + (i / (NV / 8)) * 4];   // un-pad: 4 x 16 bytes per eighth
     }
   }
   {
-    // value metadata image: Delta[ngv][R] then zero[ngv][R]
-    const int ngv = P.g.ngv;
-    const int per_plane = ngv * R;  // elements
-    for (int i = tid; i < 2 * per_plane; i += 256) {
-      const int plane = i / per_plane, rest = i - plane * per_plane;
-      o_vmeta[i] = s_vmeta[plane][rest / R][rest % R];
+    // value metadata image: Delta[ngv][R] then zero[ngv][R], 16 bytes per thread (each plane of
+    // the staging array holds 4 groups, of which the first ngv are in use)
+    const int per16 = P.g.ngv * R * (int)sizeof(META) / 16;   // 16-byte pieces of a plane: <= 128
+    if (tid < 2 * per16) {
+      const int plane = tid >= per16 ? 1 : 0, idx = tid - plane * per16;
+      reinterpret_cast<uint4*>(o_vmeta)[plane * per16 + idx] =
+          reinterpret_cast<const uint4*>(&s_vmeta[plane][0][0])[idx];
     }
-    if (tid < R) o_knorm[tid] = s_norm[tid];
+    if (tid < R * (int)sizeof(META) / 16)
+      reinterpret_cast<uint4*>(o_knorm)[tid] = reinterpret_cast<const uint4*>(&s_norm[0])[tid];
   }
   } while (false);
 

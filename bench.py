@@ -42,18 +42,18 @@ HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E bandwidth
 # each scaled by the same counter's reading for a plain 256 MiB copy kernel (summary under
 # profiles/); counters cannot be read from inside this process, so the figure is keyed by
 # the workload it was measured on and reported as null for any other.
-MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 182_276_533,
-                    ("long-b1-s128k", 2, 64): 91_587_416,
-                    ("omni-b4-g7-s64k", 2, 32): 92_673_125}
+MEASURED_TRAFFIC = {("llama3-8b-like-b8-s32k", 2, 8): 182_264_490,
+                    ("long-b1-s128k", 2, 64): 91_574_444,
+                    ("omni-b4-g7-s64k", 2, 32): 92_681_088}
 # The same kernel's mean duration over the decode steps in the committed `rocprofv3
 # --kernel-trace` summaries (the dispatch's own begin/end timestamps), for comparison with the
 # figure measured here: an event pair around a launch also holds the queue's hand-over from the
 # event marker to the dispatch and reads 2-3 us more.  Keyed like MEASURED_TRAFFIC.
-PROFILED_KERNEL_US = {("llama3-8b-like-b8-s32k", 2, 8): 33.87,
-                      ("long-b1-s128k", 2, 64): 21.86,
-                      ("omni-b4-g7-s64k", 2, 32): 27.34,
-                      ("highbatch-b64-s8k", 2, 1): 67.61,
-                      ("highbatch-b64-s8k", 4, 1): 118.03}
+PROFILED_KERNEL_US = {("llama3-8b-like-b8-s32k", 2, 8): 33.20,
+                      ("long-b1-s128k", 2, 64): 21.50,
+                      ("omni-b4-g7-s64k", 2, 32): 26.84,
+                      ("highbatch-b64-s8k", 2, 1): 66.41,
+                      ("highbatch-b64-s8k", 4, 1): 118.11}
 
 
 def profiled(w, splits, cache_bytes):
@@ -63,6 +63,17 @@ def profiled(w, splits, cache_bytes):
     return {"avg_kernel_us": us, "frac": cache_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
             "summary": "profiles/decode_mfma_%s%s.txt" % (w.name, "-int4" if w.bits == 4 else ""),
             "what": "mean over the decode steps of a rocprofv3 kernel trace of this bench (dispatch timestamps)"}
+# The encoder kernel alone on the whole-context prefill, median over the prefill launches in the
+# same kernel trace (the call timed here also holds the length-update kernel behind it).
+PROFILED_PREFILL_US = {("llama3-8b-like-b8-s32k", 2): 241.7}
+
+
+def profiled_prefill(w, pre_bytes):
+    us = PROFILED_PREFILL_US.get((w.name, w.bits))
+    if us is None:
+        return None
+    return {"kernel_us": us, "frac": pre_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "summary": "profiles/quantize_append_%s.txt" % w.name}
 EV_EVERY = 5                # every 5th launch of the decode kernel carries a HIP event pair (5 is
                             # coprime to the usual copy counts, so every cache copy gets sampled)
 LLC_BYTES = 256 << 20       # Infinity Cache
@@ -601,7 +612,10 @@ def measure(args, w, np, torch, ob, synth):
         "quantize_append_prefill": {"tokens": w.batch * w.context, "us": pre_us,
                                     "hbm_gbs": pre_bytes / (pre_us * 1e-6) / 1e9,
                                     "frac": pre_bytes / (pre_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                                    "algorithmic_bytes": pre_bytes},
+                                    "algorithmic_bytes": pre_bytes,
+                                    "what": "one oscar_quantize_append call (encoder kernel, then the small "
+                                            "length-update kernel) between two events; median over refills",
+                                    "profiled": profiled_prefill(w, pre_bytes)},
     }
     if parity:
         res["parity"] = parity

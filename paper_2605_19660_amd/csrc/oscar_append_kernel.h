@@ -14,9 +14,13 @@
 //   - the 128-point Hadamard butterfly runs 3 stages in registers and 4 stages across the
 //     row.  Lanes are labelled so that the partner of every stage is one DPP control
 //     (cg^1, cg^2: quad permutes; cg^4: half-row mirror; cg^8: row rotate by 8): no
-//     LDS-crossbar shuffles, and a butterfly is "partner + (own with the sign bit flipped
-//     in the upper lane)", which is the same fp32 add/sub the format prescribes,
-//   - the token norm is a 16-lane butterfly all-reduce over the same partners,
+//     LDS-crossbar shuffles, and a cross-lane butterfly is one instruction per element,
+//     "own += partner * (+1 | -1)", which rounds like the fp32 add/sub the format
+//     prescribes (rotate8),
+//   - the token norm is a 16-lane butterfly sum over the same partners; on the prefill
+//     path four tokens at a time, as a reduce-scatter over the quad, so that a lane takes
+//     the square root and the reciprocal of one token instead of four
+//     (key_transform_4tokens),
 //   - per-channel min/max over tokens reduce over passes (packed fp16 registers), over the
 //     4 token slots of a wave and over the 4 waves (LDS); each channel's Eq. 3-4 parameters
 //     are computed once and handed to the 16 token slots through LDS,

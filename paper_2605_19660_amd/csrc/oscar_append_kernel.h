@@ -349,8 +349,10 @@ __device__ __forceinline__ void quant_params(float mn, float mx, bool zp_min, fl
   z = zp_min ? round_meta<META>(mn) : round_meta<META>(rintf(-mn * rd));
 }
 
-// packed fp16 min / max (finite inputs); volatile: plain asm blocks of this kind have been
-// seen to be mis-scheduled
+// packed fp16 min / max (finite inputs).  volatile like every asm block of this library: the
+// one ordering problem ever found around such blocks (oscar_decode_mfma.hip, keep_tuple)
+// needed a matrix instruction in flight, which this kernel does not have, and nothing is
+// gained by letting the blocks move
 __device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
   uint32_t r;
   asm volatile("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));

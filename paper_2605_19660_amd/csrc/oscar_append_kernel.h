@@ -804,7 +804,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(sizeof(IO) 
       plo[i] = zp_min ? pz[i] : -pz[i];
       phi[i] = QMAX - pz[i];
       if ((cg & (L - 1) & ~3) == 0) {   // first quad of its value group stores the metadata
-        const int tok = (2 * qj + i) * 16 + slot, gv = cg / L;
+        const int tok = (2 * qj + i) * 16 + slot, gv = cg >> (L == 4 ? 2 : L == 8 ? 3 : 4);
         s_vmeta[0][gv][tok_meta_pos(tok)] = from_f32<META>(df);
         s_vmeta[1][gv][tok_meta_pos(tok)] = from_f32<META>(pz[i]);
       }

@@ -121,6 +121,32 @@ def test_prefill_bitexact_ragged(io, meta, bits, kg, vg):
     assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
 
 
+def test_prefill_on_a_grid_past_the_ticket_limit_then_single_tokens():
+    """A prefill of more than 1024 workgroups updates the lengths with the second, small kernel
+    (the library drops the ticket for such grids); the one-token appends behind it draw tickets
+    again.  Lengths, every code and the residual must match the oracle after each of them."""
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=4, n_q_heads=32, n_kv_heads=8, context=128 * 40 + 37)
+    assert w.n_kv_heads * ((128 + w.context) // 128) * w.batch > 1024
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 44)
+    n0 = w.context - 2
+    ob.quantize_append(g, to_dev(k[:, :n0], w.io_dtype), to_dev(v[:, :n0], w.io_dtype), eager=True,
+                       max_seq_len_hint=0)
+    o.append(k[:, :n0], v[:, :n0], eager=True)
+    assert_cache_equal(g, o, w)
+    assert int(g.tickets.item()) == 0
+    for t in (n0, n0 + 1):
+        ob.quantize_append(g, to_dev(k[:, t:t + 1], w.io_dtype), to_dev(v[:, t:t + 1], w.io_dtype))
+        o.append(k[:, t:t + 1], v[:, t:t + 1])
+        assert_cache_equal(g, o, w)
+        assert int(g.tickets.item()) == 0
+    q = synth.make_q(w)
+    out = ob.decode_attn(g, to_dev(q, w.io_dtype), max_seq_len_hint=w.context)
+    assert_decode_close(out.cpu().numpy(), o.decode_attn(q))
+    assert int(g.dev_status.item()) == 0
+
+
 def test_incremental_appends_deferred_flush_and_ragged_new_lens():
     """Mixed chunk sizes, per-sequence new_lens, flush of a full residual deferred to the
     next append (the block stays 16-bit through the attention in between)."""

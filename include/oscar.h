@@ -115,7 +115,8 @@ typedef struct oscar_config {
  *   v_meta  : Delta[head_dim/v_group][R] then zero[head_dim/v_group][R] (meta_dtype),
  *             token axis as in k_norms
  * Residual part, indexed [sequence][kv head]:
- *   res_k   : [R][head_dim] fp16, rotated and normalized keys K_u
+ *   res_k   : [R][head_dim] fp16, rotated and normalized keys K_u (an element that is
+ *             exactly zero may be stored as -0)
  *   res_v   : [R][head_dim] io_dtype
  *   res_norm: [R] meta_dtype
  * State: seq_lens[b] = tokens held for sequence b; res_lens[b] of them (0..R,

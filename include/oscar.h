@@ -221,6 +221,9 @@ int oscar_quantize_append(const void *k, const void *v, int32_t T, const int32_t
  *   num_splits : split-K factor over the sequence (<= 512), 0 = oscar_decode_auto_splits
  *   workspace  : device scratch of at least oscar_decode_workspace_bytes(...)
  * A sequence with seq_lens[b] == 0 yields zeros.
+ * Two launches (split-K partial pass, reduce pass); with a single split the matrix-core kernel
+ * writes `out` itself and the reduce launch is left out (same bits: the same sums, divided the
+ * same way; the workspace is still required and may then stay untouched).
  * Two kernels sit behind this call: the matrix-core one (fp16 metadata; scale_mode L2 or MAX,
  * i.e. keys scaled into [-1, 1]) and a generic plain-ALU one for every other configuration
  * (fp32 metadata; scale_mode NONE or MEAN_ABS); both are checked against the same
@@ -270,7 +273,8 @@ int oscar_debug_force_generic_decode(int32_t on);
 
 /* The two passes of oscar_decode_attn as separate calls, for callers that want to time
  * or overlap them: oscar_decode_attn(...) == partial(...) followed by reduce(...) on the
- * same stream with the same num_splits (> 0 here) and workspace.
+ * same stream with the same num_splits (> 0 here) and workspace (these two always go through
+ * the workspace, also for a single split).
  * (Split-K partial pass: per (sequence, kv head, split) online-softmax attention over a
  * range of pages, all query heads of the group sharing each packed tile; reduce pass:
  * log-sum-exp merge of the splits.) */

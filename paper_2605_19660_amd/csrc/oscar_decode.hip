@@ -423,9 +423,12 @@ static int check_decode_cache(const oscar_cache* cache) {
   return OSCAR_OK;
 }
 
+// out != nullptr (callers pass it for a single split only): the matrix-core kernel writes the
+// attention output itself and *wrote_out is set; the generic kernel always writes records.
 static int launch_partial(const void* q, const oscar_cache* cache, void* out, int32_t out_dtype,
                           float softmax_scale, int32_t num_splits, void* workspace,
-                          size_t workspace_bytes, void* stream, oscar_timer* timer) {
+                          size_t workspace_bytes, void* stream, oscar_timer* timer,
+                          int* wrote_out = nullptr) {
   int rc = check_decode_cache(cache);
   if (rc != OSCAR_OK) return rc;
   if (!q || num_splits <= 0 || num_splits > 512) return OSCAR_ERR_INVALID_ARG;
@@ -445,10 +448,15 @@ static int launch_partial(const void* q, const oscar_cache* cache, void* out, in
   const int gq = cache->cfg.n_q_heads / cache->cfg.n_kv_heads;
   dim3 grid(num_splits, cache->cfg.n_kv_heads, cache->batch);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (out && num_splits != 1) return OSCAR_ERR_INVALID_ARG;
+  if (wrote_out) *wrote_out = 0;
   rc = oscar_launch_decode_mfma(&P, gq, grid, st, e0, e1);
-  if (rc == OSCAR_ERR_UNSUPPORTED)
+  if (rc == OSCAR_OK && out && wrote_out) *wrote_out = 1;
+  if (rc == OSCAR_ERR_UNSUPPORTED) {
+    P.out = nullptr;
     rc = (cache->cfg.bits == 2) ? launch_gq<2>(P, gq, grid, st, e0, e1)
                                 : launch_gq<4>(P, gq, grid, st, e0, e1);
+  }
   if (rc != OSCAR_OK) return rc;
   if (hipGetLastError() != hipSuccess) return OSCAR_ERR_HIP;
   if (timer) timer->armed = 1;
@@ -533,9 +541,11 @@ extern "C" int oscar_decode_attn(const void* q, const oscar_cache* cache, void* 
   if (out_dtype != OSCAR_F32 && out_dtype != cache->cfg.io_dtype) return OSCAR_ERR_INVALID_ARG;
   if (num_splits == 0)
     num_splits = oscar_decode_auto_splits(&cache->cfg, cache->batch, max_seq_len_hint);
-  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
-                      workspace_bytes, stream, nullptr);
-  if (rc != OSCAR_OK) return rc;
+  // a single split needs no reduce pass: the matrix-core kernel then writes `out` itself
+  int wrote_out = 0;
+  rc = launch_partial(q, cache, num_splits == 1 ? out : nullptr, out_dtype, softmax_scale,
+                      num_splits, workspace, workspace_bytes, stream, nullptr, &wrote_out);
+  if (rc != OSCAR_OK || wrote_out) return rc;
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
                                   stream);
 }
@@ -559,9 +569,10 @@ extern "C" int oscar_decode_step(const void* k_new, const void* v_new, const voi
   if (!workspace || workspace_bytes < need) return OSCAR_ERR_WORKSPACE;
   rc = oscar_quantize_append(k_new, v_new, 1, nullptr, cache, max_seq_len_hint - 1, 0u, stream);
   if (rc != OSCAR_OK) return rc;
-  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, workspace,
-                      workspace_bytes, stream, partial_timer);
-  if (rc != OSCAR_OK) return rc;
+  int wrote_out = 0;
+  rc = launch_partial(q, cache, num_splits == 1 ? out : nullptr, out_dtype, softmax_scale,
+                      num_splits, workspace, workspace_bytes, stream, partial_timer, &wrote_out);
+  if (rc != OSCAR_OK || wrote_out) return rc;
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, workspace, workspace_bytes,
                                   stream);
 }
@@ -610,9 +621,11 @@ extern "C" int oscar_decode_attn_noalloc(const void* q, const oscar_cache* cache
   if (rc != OSCAR_OK) return rc;
   // every record of the partials (batch x query head x split) is written by the partial pass
   // before the reduce pass reads it, so nothing of the previous call's contents has to be cleared
-  rc = launch_partial(q, cache, nullptr, OSCAR_F32, softmax_scale, num_splits, ws,
-                      (size_t)OSCAR_NOALLOC_SCRATCH_BYTES, stream, nullptr);
-  if (rc != OSCAR_OK) return rc;
+  int wrote_out = 0;
+  rc = launch_partial(q, cache, num_splits == 1 ? out : nullptr, out_dtype, softmax_scale,
+                      num_splits, ws, (size_t)OSCAR_NOALLOC_SCRATCH_BYTES, stream, nullptr,
+                      &wrote_out);
+  if (rc != OSCAR_OK || wrote_out) return rc;
   return oscar_decode_attn_reduce(cache, out, out_dtype, num_splits, ws,
                                   (size_t)OSCAR_NOALLOC_SCRATCH_BYTES, stream);
 }

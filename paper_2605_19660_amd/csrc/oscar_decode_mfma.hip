@@ -1035,6 +1035,10 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   // a thread owns one channel of every second head (the head parity is wave-uniform, so no
   // lane idles); the reads of a head are independent and go out together
   const int ch = tid & (D - 1), hh = __builtin_amdgcn_readfirstlane(tid >> 7);
+  // With a single split the record is the result: the host passes the output tensor and
+  // launches no reduce pass.  acc / L below are the record's own numbers, divided as the
+  // reduce pass divides them, so both routes give the same bits.
+  const bool direct = P.out != nullptr;
 #pragma unroll
   for (int k = 0; k < OSCAR_MAX_GQA / 2; ++k) {
     const int h = hh + 2 * k;
@@ -1052,11 +1056,25 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         for (int w = 0; w < 4; ++w)
           if (m[w] != -INFINITY) acc += o[w] * __builtin_amdgcn_exp2f(m[w] - M);
       }
-      const size_t rec = ((size_t)b * Hq + (size_t)kvh * gq + h) * P.num_splits + split;
-      P.ws[rec * WS_STRIDE + ch] = acc;
+      const size_t unit = (size_t)b * Hq + (size_t)kvh * gq + h;
+      if (direct) {
+        float L = 0.0f;
+        if (M != -INFINITY) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            if (m[w] != -INFINITY) L += s_wl[w][h] * __builtin_amdgcn_exp2f(m[w] - M);
+        }
+        const float res = L > 0.0f ? acc / L : 0.0f;
+        const size_t oi = unit * D + ch;
+        if (P.out_dtype == OSCAR_F32) reinterpret_cast<float*>(P.out)[oi] = res;
+        else if (P.out_dtype == OSCAR_BF16) reinterpret_cast<__hip_bfloat16*>(P.out)[oi] = __float2bfloat16(res);
+        else reinterpret_cast<__half*>(P.out)[oi] = __float2half_rn(res);
+      } else {
+        P.ws[(unit * P.num_splits + split) * WS_STRIDE + ch] = acc;
+      }
     }
   }
-  if (tid < gq) {
+  if (!direct && tid < gq) {
     const int h = tid;
     float M = -INFINITY;
 #pragma unroll

@@ -408,6 +408,35 @@ def test_decode_long_stream_one_split_crosses_block_table_chunks(bits):
         assert_decode_close(out.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("hq,hkv,bits,out_dt", [(8, 2, 2, "f32"), (28, 4, 2, "bf16"), (16, 2, 4, "f32")])
+def test_single_split_writes_the_output_itself_with_the_bits_of_the_two_pass_route(hq, hkv, bits, out_dt):
+    """One split: oscar_decode_attn lets the matrix-core kernel write `out` and launches no reduce
+    pass.  The separate partial + reduce calls always go through the workspace; both routes must
+    give the same bits, ragged lengths, an empty and a residual-only sequence included."""
+    torch = _torch()
+    ob = _ob()
+    w = synth.LLAMA8B_32K.replace(batch=4, n_q_heads=hq, n_kv_heads=hkv, context=128 * 5 + 61, bits=bits)
+    k, v = synth.make_kv_batch(w)
+    g, o = make_pair(w, 8)
+    nl = np.asarray([w.context, 128 * 2 + 3, 0, 77], np.int32)
+    ob.quantize_append(g, to_dev(k, w.io_dtype), to_dev(v, w.io_dtype), eager=True,
+                       new_lens=torch.from_numpy(nl).cuda(), max_seq_len_hint=0)
+    o.append(k, v, new_lens=nl, eager=True)
+    q = to_dev(synth.make_q(w), w.io_dtype)
+    dt = {"f32": torch.float32, "bf16": torch.bfloat16}[out_dt]
+    ws = torch.zeros(ob.decode_workspace_bytes(g.cfg, w.batch, 1), dtype=torch.uint8, device="cuda")
+    direct = torch.full((w.batch, hq, w.head_dim), 7.0, dtype=dt, device="cuda")
+    ob.decode_attn(g, q, out=direct, max_seq_len_hint=w.context, num_splits=1, workspace=ws)
+    assert not ws.any().item(), "the single-split route left records in the workspace"
+    two_pass = torch.full_like(direct, 9.0)
+    ob.decode_attn_partial(g, q, ws, 1)
+    ob.decode_attn_reduce(g, two_pass, ws, 1)
+    assert torch.equal(direct.view(torch.uint8), two_pass.view(torch.uint8))
+    assert not direct[2].any().item()                          # the empty sequence: zeros
+    if out_dt == "f32":
+        assert_decode_close(direct.cpu().numpy(), o.decode_attn(synth.make_q(w)))
+
+
 @pytest.mark.parametrize("scale", [2.0 ** -12, 2.0 ** 6])
 def test_decode_extreme_value_magnitudes(scale):
     """Values (and so their step sizes) far from 1: the per-page power-of-two operand scaling of

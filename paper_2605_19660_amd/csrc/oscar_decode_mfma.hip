@@ -15,9 +15,12 @@
 //    bit offset s of an fp16 lane's mantissa (exponent field zero) is the subnormal number
 //    c * 2^s * 2^-24, and the MFMA keeps fp16 subnormals.  2^s is divided out of the other
 //    operand.  Offsets stay near the top of the mantissa (see slot_bitpos).
-//  * The other operand (Q_h*Delta_k, resp. p*Delta_v) is fp32 split into fp16 hi + lo,
-//    carried as two rows of the 16-row MFMA tile (rows are otherwise idle for GQA <= 8),
-//    so products are exact and accumulation is fp32.
+//  * The other operand (Q_h*Delta_k, resp. p*Delta_v) is carried as fp16 hi + lo limbs in two
+//    rows of the 16-row MFMA tile (rows are otherwise idle for GQA <= 8): hi + lo equals the
+//    fp32 product to ~2^-21, the MFMA's products with the codes are exact and accumulation
+//    is fp32.  The limbs come from packed fp16 arithmetic on a multiplicand split once
+//    (mul_limbs_packed; mul_split_hi_lo is the mixed-precision form it replaced, still built
+//    with OSCAR_LIMBS_PACKED = 0).
 //  * Zero-points are subtracted analytically in fp32 (the two right-hand sums above).
 //
 // Work decomposition: grid (split, kv head, sequence); 4 waves per workgroup, every wave
@@ -170,6 +173,57 @@ __device__ __forceinline__ void mul_split_hi_lo(const float (&x)[8], const uint4
         "v"(y.x), "v"(y.y), "v"(y.z), "v"(y.w));
   hi = make_uint4(h0, h1, h2, h3);
   lo = make_uint4(l0, l1, l2, l3);
+}
+
+// The same limbs from packed fp16 arithmetic, for a multiplicand that serves several
+// multipliers (the probabilities of a page against the step sizes of every value group, the
+// queries against the step sizes of every page): x is split once into fp16 xh + xl (xl holds
+// what the rounding of xh left over: x = xh + xl to 2^-22), and per multiplier
+//   hi = xh * y,  e = fma(xh, y, -hi)  (the rounding error of that product, an fp16 number
+//   unless it falls below the subnormal range),  lo = fma(xl, y, e)
+// -- three packed instructions per two elements where the mixed-precision form takes four of
+// twice the issue time.  hi + lo equals the product to ~2^-21.
+#ifndef OSCAR_LIMBS_PACKED
+#define OSCAR_LIMBS_PACKED 1
+#endif
+__device__ __forceinline__ void split_to_halves(const float (&x)[8], uint4& xh, uint4& xl) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x2 v = {x[2 * i], x[2 * i + 1]};
+    const half2v hh = __builtin_convertvector(v, half2v);
+    const f32x2 r = {x[2 * i] - (float)hh[0], x[2 * i + 1] - (float)hh[1]};   // exact
+    h[i] = __builtin_bit_cast(uint32_t, hh);
+    l[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, half2v));
+  }
+  xh = make_uint4(h[0], h[1], h[2], h[3]);
+  xl = make_uint4(l[0], l[1], l[2], l[3]);
+}
+__device__ __forceinline__ uint4 scale_halves(const uint4& y, half2v k) {
+  const uint32_t c[4] = {y.x, y.y, y.z, y.w};
+  uint32_t r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, c[i]) * k);
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+__device__ __forceinline__ void mul_limbs_packed(const uint4& xh, const uint4& xl, const uint4& y,
+                                                 uint4& hi, uint4& lo) {
+  const uint32_t a[4] = {xh.x, xh.y, xh.z, xh.w}, b[4] = {xl.x, xl.y, xl.z, xl.w};
+  const uint32_t c[4] = {y.x, y.y, y.z, y.w};
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const half2v ah = __builtin_bit_cast(half2v, a[i]), al = __builtin_bit_cast(half2v, b[i]);
+    const half2v yy = __builtin_bit_cast(half2v, c[i]);
+    const half2v p = ah * yy;
+    const half2v e = __builtin_elementwise_fma(ah, yy, -p);
+    const half2v q = __builtin_elementwise_fma(al, yy, e);
+    h[i] = __builtin_bit_cast(uint32_t, p);
+    l[i] = __builtin_bit_cast(uint32_t, q);
+  }
+  hi = make_uint4(h[0], h[1], h[2], h[3]);
+  lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // Products of packed fp16 pairs in fp32, and fp16 * fp32, without widening instructions:
@@ -707,6 +761,9 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
   // ---- per-lane constants ----
   // writer role for the key operand: positions 8n..8n+7 of heads q4 (+4)
   float qr[HP][8], qs[HP][8], ps[HP];
+#if OSCAR_LIMBS_PACKED
+  uint4 qsh[HP], qsl[HP];   // qs as fp16 limbs
+#endif
 #pragma unroll
   for (int s = 0; s < HP; ++s) {
     const int h = q4 + 4 * s;
@@ -726,6 +783,9 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) qs[s][i] = ldexpf(qr[s][i], xh - slot_bitpos(BITS, n & 3, i));
     ps[s] = ldexpf(1.0f, 24 - xh);
+#if OSCAR_LIMBS_PACKED
+    split_to_halves(qs[s], qsh[s], qsl[s]);
+#endif
     if constexpr (HP == 2) {
       s_qr[wave][s][0][lane] = make_float4(qr[s][0], qr[s][1], qr[s][2], qr[s][3]);
       s_qr[wave][s][1][lane] = make_float4(qr[s][4], qr[s][5], qr[s][6], qr[s][7]);
@@ -805,7 +865,11 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
           }
           bias[s] = row16_sum(bp);
           uint4 hi, lo;
+#if OSCAR_LIMBS_PACKED
+          mul_limbs_packed(qsh[s], qsl[s], kr.kd[g], hi, lo);
+#else
           mul_split_hi_lo(qs[s], kr.kd[g], hi, lo);
+#endif
           // (rows of heads past the group hold zeros either way: their queries are zero)
           const int h = q4 + 4 * s;
           *reinterpret_cast<uint4*>(&A_tab[row_hi(h)][8 * n]) = hi;
@@ -928,17 +992,32 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
     xv_cur = xv;
 
     // ---- P V, one value group at a time through the wave's LDS table ----
-    const float pscale = ldexpf(1.0f, xv);
+    [[maybe_unused]] const float pscale = ldexpf(1.0f, xv);
     float pc[HP][8];   // p * 2^(xv - slot offset): the value operand before Delta_v
 #pragma unroll
     for (int s = 0; s < HP; ++s)
 #pragma unroll
-      for (int T = 0; T < 8; ++T) pc[s][T] = S[s][T] * (vsc0[T] * pscale);
+      for (int T = 0; T < 8; ++T)
+        pc[s][T] = S[s][T] * (vsc0[T] * (OSCAR_LIMBS_PACKED ? 16384.0f : pscale));
+#if OSCAR_LIMBS_PACKED
+    // The probabilities are split as p * 2^14 (at most 2^14, whatever the page's step sizes
+    // are); the rest of the page's power of two goes to the step sizes, whose largest then
+    // sits in [2^-2, 2^-1): an exact scaling unless a step size is 2^12 times smaller than
+    // the page's largest.
+    uint4 pch[HP], pcl[HP];
+#pragma unroll
+    for (int s = 0; s < HP; ++s) split_to_halves(pc[s], pch[s], pcl[s]);
+    const _Float16 ysc = (_Float16)ldexpf(1.0f, xv - 14);
+    const half2v ysc2 = {ysc, ysc};
+#endif
 #pragma unroll
     for (int g = 0; g < NGV; ++g) {
       float dz[8];
       if constexpr (zp_min) neg_widen8(vr.vz[g], dz);
       else mix_mul8(vr.vd[g], vr.vz[g], dz);
+#if OSCAR_LIMBS_PACKED
+      const uint4 yd = scale_halves(vr.vd[g], ysc2);
+#endif
 #pragma unroll
       for (int s = 0; s < HP; ++s) {
         float acc_b = 0.0f;
@@ -946,7 +1025,11 @@ void oscar_decode_mfma_kernel(DecodeParams P, int gq) {
         for (int T = 0; T < 8; ++T) acc_b = fmaf(S[s][T], dz[T], acc_b);
         bv[s][g] += acc_b;
         uint4 hi, lo;
+#if OSCAR_LIMBS_PACKED
+        mul_limbs_packed(pch[s], pcl[s], yd, hi, lo);
+#else
         mul_split_hi_lo(pc[s], vr.vd[g], hi, lo);
+#endif
         // (heads past the group produce finite values in rows nobody reads back)
         const int h = q4 + 4 * s;
         *reinterpret_cast<uint4*>(&P_tab[row_hi(h)][8 * n]) = hi;

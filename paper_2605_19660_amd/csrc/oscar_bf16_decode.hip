@@ -15,6 +15,13 @@
 
 namespace {
 
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+
 constexpr int D = OSCAR_D;
 constexpr int WS_STRIDE = D + 2;
 constexpr int TOK_STEP = 4;   // tokens per row and step
@@ -103,8 +110,9 @@ __global__ __launch_bounds__(256) void oscar_plain_decode_partial_kernel(PlainPa
 #pragma unroll
       for (int j = 0; j < TOK_STEP; ++j) {
         const int t = min(t_first + 16 * j, tok1 - 1);
-        kr[j] = *reinterpret_cast<const uint4*>(kbase + seq_off + (size_t)t * row_stride);
-        vr[j] = *reinterpret_cast<const uint4*>(vbase + seq_off + (size_t)t * row_stride);
+        // (read once per launch: non-temporal loads, as in the packed-cache kernel)
+        kr[j] = load_stream16(kbase + seq_off + (size_t)t * row_stride);
+        vr[j] = load_stream16(vbase + seq_off + (size_t)t * row_stride);
       }
     };
     uint4 kcur[TOK_STEP], vcur[TOK_STEP];

@@ -1,4 +1,4 @@
-"""Static check of the compiled matrix-core decode kernels for one hazard the compiler cannot see.
+"""Static checks of the compiled kernels for two hazards the compiler cannot see.
 
     python -m paper_2605_19660_amd.check_asm_hazards          (compiles to assembly, then scans)
 
@@ -17,6 +17,13 @@ consumed (`keep_tuple`), and this scan checks the compiler's output for what is 
     compiler has inserted the wait states) proves that it has retired and ends the walk; an
     instruction inside ASMSTART/ASMEND that writes (or reads) one of them earlier, within
     `window` wait states, is reported.
+
+The second check (every translation unit with DPP instructions in asm blocks): a DPP operand
+must not be read in the two issue slots after a vector instruction wrote that register; the
+compiler inserts the wait states for its own DPP instructions and for nothing inside an asm
+block.  `scan_dpp` reports every DPP instruction between ASMSTART and ASMEND whose DPP source
+register was written by one of the two vector instructions issued before it (an `s_nop n`
+counts as n + 1 slots).
 """
 from __future__ import annotations
 
@@ -28,6 +35,7 @@ import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = ("oscar_decode_mfma.hip", "oscar_decode_mfma_zpmin.hip")
+DPP_SOURCES = SOURCES + ("oscar_quantize.hip",)    # the encoder and the stand-alone rotations
 
 
 def _regs(tok: str) -> set[int]:
@@ -98,12 +106,47 @@ def scan(asm_text: str, window: int = WINDOW) -> list[tuple]:
     return found
 
 
+def scan_dpp(asm_text: str) -> list[tuple]:
+    lines = asm_text.split("\n")
+    found, flag, kernel = [], False, None
+    recent: list[tuple[set[int], int]] = []      # (registers written, line) of the last vector instructions
+    slots_since: list[int] = []                   # issue slots between each of them and now
+    hist: list[tuple[set[int], int, int]] = []    # (written registers, line number, slots ago)
+    for i, l in enumerate(lines):
+        m = re.match(r"^(_Z\S+):", l)
+        if m:
+            kernel, hist = m.group(1), []
+        if "#ASMSTART" in l:
+            flag = True
+        if "#ASMEND" in l:
+            flag = False
+        t = l.strip()
+        if not t or t[0] in ";." or t.endswith(":"):
+            if t.endswith(":") and not t.startswith(";"):
+                hist = []                          # control flow joins: the compiler's own rules apply
+            continue
+        op = t.split()[0]
+        step = int(t.split()[1]) + 1 if op == "s_nop" else 1
+        if flag and "_dpp" in op:
+            ops = _operands(t)
+            src = ops[1] if len(ops) > 1 else set()      # the DPP operand is the first source
+            for regs, ln, ago in hist:
+                if ago < 2 and regs & src:
+                    found.append((kernel, ln + 1, lines[ln].strip(), i + 1, t, ago))
+        hist = [(r, ln, ago + step) for r, ln, ago in hist if ago + step < 4]
+        if op.startswith("v_") and not op.startswith("v_cmp"):
+            ops = _operands(t)
+            if ops:
+                hist.append((set(ops[0]), i, 0))
+    return found
+
+
 def compile_to_asm(source: str) -> str:
-    from .build import COMMON, CSRC
+    from .build import COMMON, CSRC, SOURCES as BUILD_SOURCES
     with tempfile.TemporaryDirectory() as d:
         out = os.path.join(d, "k.s")
-        cmd = ["hipcc", *[c for c in COMMON if c != "-fPIC"], "--cuda-device-only", "-S",
-               os.path.join(CSRC, source), "-o", out]
+        cmd = ["hipcc", *[c for c in COMMON if c != "-fPIC"], *BUILD_SOURCES.get(source, []),
+               "--cuda-device-only", "-S", os.path.join(CSRC, source), "-o", out]
         subprocess.run(cmd, check=True, capture_output=True)
         return open(out).read()
 
@@ -111,14 +154,21 @@ def compile_to_asm(source: str) -> str:
 def main() -> int:
     from concurrent.futures import ThreadPoolExecutor
     bad = 0
-    with ThreadPoolExecutor(max_workers=2) as ex:
-        texts = list(ex.map(compile_to_asm, SOURCES))
-    for src, text in zip(SOURCES, texts):
-        n_mfma = text.count("\tv_mfma")
-        found = scan(text)
-        print("%s: %d matrix instructions, %d asm writes into a result still in flight" % (src, n_mfma, len(found)))
-        for k, i, t, j, tj, w in found[:20]:
-            print("  %s\n    line %d: %s\n    line %d (+%d wait states): %s" % (k, i, t, j, w, tj))
+    with ThreadPoolExecutor(max_workers=3) as ex:
+        texts = list(ex.map(compile_to_asm, DPP_SOURCES))
+    for src, text in zip(DPP_SOURCES, texts):
+        if src in SOURCES:
+            n_mfma = text.count("\tv_mfma")
+            found = scan(text)
+            print("%s: %d matrix instructions, %d asm writes into a result still in flight" % (src, n_mfma, len(found)))
+            for k, i, t, j, tj, w in found[:20]:
+                print("  %s\n    line %d: %s\n    line %d (+%d wait states): %s" % (k, i, t, j, w, tj))
+            bad += len(found)
+        n_dpp = len(re.findall(r"#ASMSTART(?:(?!#ASMEND).)*?_dpp", text, re.S))
+        found = scan_dpp(text)
+        print("%s: %d asm blocks with DPP instructions, %d DPP reads inside two slots of the write" % (src, n_dpp, len(found)))
+        for k, i, t, j, tj, ago in found[:20]:
+            print("  %s\n    line %d: %s\n    line %d (%d slots later): %s" % (k, i, t, j, ago, tj))
         bad += len(found)
     return 1 if bad else 0
 

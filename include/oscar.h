@@ -127,8 +127,8 @@ typedef struct oscar_config {
  * dropped for that sequence.
  * tickets (may be NULL): a device int32[1], zeroed once by the caller. With it the last
  * workgroup of oscar_quantize_append to finish also advances seq_lens / res_lens (one
- * launch) and leaves the ticket zero again; without it, and for grids of more than 1024
- * workgroups (prefills), the length update is a second, tiny launch. */
+ * launch) and leaves the ticket zero again; without it, and for appends of 128 tokens or more
+ * whose grid exceeds 1024 workgroups (prefills), the length update is a second, tiny launch. */
 typedef struct oscar_cache {
   oscar_config cfg;
   int32_t batch;

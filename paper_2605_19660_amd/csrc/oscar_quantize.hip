@@ -4,7 +4,8 @@
 
 namespace {
 
-// largest grid whose length update rides on the encoder launch (oscar_quantize_append)
+// largest grid of a multi-block append whose length update rides on the encoder launch
+// (oscar_quantize_append)
 constexpr size_t kTicketMaxWorkgroups = 1024;
 
 // Stand-alone rotation kernel: 16 vectors of 128 channels per workgroup (one DPP row each).
@@ -315,9 +316,9 @@ extern "C" int oscar_quantize_append(const void* k, const void* v, int32_t T,
   dim3 grid(cache->cfg.n_kv_heads, nblk, cache->batch);
   // The ticket saves a launch, and a workgroup that draws one holds its registers and LDS until
   // the counter's answer is back.  Worth it where a launch is what the call costs (a decode
-  // step's one-token append); a grid of many rounds of workgroups updates the lengths with the
-  // small second kernel instead.
-  if ((size_t)grid.x * grid.y * grid.z > kTicketMaxWorkgroups) P.c.tickets = nullptr;
+  // step's one-token append, at any batch size); a multi-block append whose grid runs in many
+  // rounds of workgroups updates the lengths with the small second kernel instead.
+  if (nblk > 1 && (size_t)grid.x * grid.y * grid.z > kTicketMaxWorkgroups) P.c.tickets = nullptr;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (cache->cfg.norm_scope == OSCAR_NORM_ALL_KV_HEADS)
     rc = oscar_launch_append_all_heads(P, grid, st);

@@ -19,7 +19,7 @@ import sys
 import time
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-STAMP_NAMES = {0: "entry", 1: "arguments", 2: "first page asked for", 3: "queries rotated", 4: "prologue done",
+STAMP_NAMES = {0: "entry", 1: "arguments", 2: "first page (key side) asked for", 3: "queries rotated", 4: "prologue done",
                5: "first logits", 24: "loop done", 25: "results in LDS", 26: "barrier passed",
                27: "record written"}
 

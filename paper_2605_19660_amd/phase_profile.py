@@ -28,6 +28,8 @@ def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--residual", type=int, default=0,
+                    help="tokens appended one call behind the prefill (0..128): they stay in the 16-bit window")
     args = ap.parse_args()
 
     lib_path = os.path.join(HERE, "liboscar_hip_stamps.so")
@@ -45,18 +47,22 @@ def main() -> None:
     cfg = ob.Config(w.n_q_heads, w.n_kv_heads, w.head_dim, w.bits, w.k_group, w.v_group, w.page_size,
                     io, meta)
     kd, vd = synth.make_kv_device(w)
-    pages = w.context // w.page_size + 2
+    pages = w.context // w.page_size + 3
+    if not 0 <= args.residual <= w.page_size:
+        sys.exit("--residual must be 0..%d" % w.page_size)
     cache_mb = w.batch * w.n_kv_heads * w.context * synth.cache_bytes_per_token_kvh(w) / 1e6
     n_copies = max(2, int(512 / cache_mb) + 2)
     caches = []
     for _ in range(n_copies):
         c = ob.Cache(cfg, w.batch, pages)
         ob.quantize_append(c, kd, vd, eager=True, max_seq_len_hint=0)
+        if args.residual:
+            ob.quantize_append(c, kd[:, :args.residual].contiguous(), vd[:, :args.residual].contiguous())
         caches.append(c)
     del kd, vd
     q = torch.from_numpy(synth.make_q(w)).cuda().to(ob.torch_dtype(io)).contiguous()
     out = torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.float32, device="cuda")
-    splits = ob.decode_auto_splits(cfg, w.batch, w.context)
+    splits = ob.decode_auto_splits(cfg, w.batch, w.context + args.residual)
     ws = torch.empty(ob.decode_workspace_bytes(cfg, w.batch, splits), dtype=torch.uint8, device="cuda")
     lib = ob.lib()
     lib.oscar_debug_read_stamps.argtypes = [C.c_void_p, C.c_size_t]
@@ -65,7 +71,7 @@ def main() -> None:
     pages_per_wave = -(-(w.context // w.page_size) // (4 * splits))
     print("# workload %s: batch %d, %d kv heads, context %d, %d-bit; %d splits -> %d workgroups, %d pages per wave"
           % (w.name, w.batch, w.n_kv_heads, w.context, w.bits, splits, splits * w.n_kv_heads * w.batch,
-             pages_per_wave))
+             pages_per_wave) + ("; %d tokens in the 16-bit residual window" % args.residual if args.residual else ""))
     print("# us after the earliest entry among the sampled workgroups; slots 0-3: splits 0-3 of (sequence 0, kv head 0),")
     print("# the first workgroups of the grid; slots 4-7: splits 0-3 of the last sequence's last kv head")
     for rep in range(args.reps):
